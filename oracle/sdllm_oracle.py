@@ -31,6 +31,8 @@ default is listed first):
   k_rounding   "ceil" (quota ceil(r*n)) or "floor" (Alg. 1 step 9).
   ties         the lower position wins; retained positions are reported ascending.
   GQA          query head h reads KV head h // G; one index set per (batch, KV head).
+  evict_scope  "bidirectional" (Alg. 1) or "prefix_only" (Alg. 4, the prefix-sparse ablation:
+               only K_{:o} is scored and ranked, every suffix entry is kept).
 
 Parity pins (tests/test_oracle_*.py): brute-force loops on tiny inputs, r = 1
 reproducing dense attention, closed forms (zero queries, one-hot values),
@@ -55,6 +57,8 @@ CEIL = "ceil"
 FLOOR = "floor"
 MAX_POOL = "max"
 AVG_POOL = "avg"
+BIDIRECTIONAL = "bidirectional"
+PREFIX_ONLY = "prefix_only"
 
 
 # ----------------------------------------------------------------------------- schedule
@@ -186,12 +190,23 @@ def select_indices(pooled: np.ndarray, seq_len: int, block_off: int, block_len: 
 
 def score_select(q_blk: np.ndarray, k_full: np.ndarray, block_off: int, block_len: int, r: float,
                  s: int, score_mode: str = SOFTMAX_MEAN, select_mode: str = PER_SEGMENT,
-                 k_rounding: str = CEIL, scale: float | None = None, pool_kind: str = MAX_POOL):
-    """Alg. 1 up to the index set.  q_blk [Hq,b,d], k_full [Hkv,L,d].
+                 k_rounding: str = CEIL, scale: float | None = None, pool_kind: str = MAX_POOL,
+                 evict_scope: str = BIDIRECTIONAL):
+    """Alg. 1 (or Alg. 4 for evict_scope == "prefix_only") up to the index set.
+    q_blk [Hq,b,d], k_full [Hkv,L,d].
 
-    Returns (idx [Hkv, k] int64 ascending absolute positions, pooled [Hkv, N], score [Hkv, N]).
+    Returns (idx [Hkv, k] int64 ascending absolute positions, pooled [Hkv, N'], score [Hkv, N'])
+    where N' is the number of scored candidates (N, or N_pre for prefix-only eviction).
     """
     hkv, L, _ = k_full.shape
+    if evict_scope == PREFIX_ONLY:
+        # Alg. 4: K_f = K_{:o} is scored and ranked; K_r = K_{o+b:} is appended whole
+        k_prefix_and_block = k_full[:, :block_off + block_len]
+        idx, pooled, score = score_select(q_blk, k_prefix_and_block, block_off, block_len, r, s, score_mode,
+                                          PER_SEGMENT, k_rounding, scale, pool_kind)
+        suffix = np.arange(block_off + block_len, L, dtype=np.int64)
+        idx = np.concatenate([idx, np.broadcast_to(suffix, (hkv, suffix.size))], axis=1)
+        return idx, pooled, score
     score = saliency_score(q_blk, k_full, block_off, block_len, score_mode, scale)
     pooled = np.stack([pool_scores(score[g], block_off, s, select_mode, pool_kind) for g in range(hkv)])
     idx = np.stack([select_indices(pooled[g], L, block_off, block_len, r, select_mode, k_rounding)[0]
@@ -241,7 +256,7 @@ def dense_block_attention(q_blk, k_full, v_full, scale=None) -> np.ndarray:
 # ----------------------------------------------------------------------------- one block
 def block_step(step_in_block: int, delay: int, q_blk, k_in, v_in, cache, *, block_off: int,
                block_len: int, r: float, s: int, score_mode=SOFTMAX_MEAN, select_mode=PER_SEGMENT,
-               k_rounding=CEIL, scale=None, pool_kind=MAX_POOL):
+               k_rounding=CEIL, scale=None, pool_kind=MAX_POOL, evict_scope=BIDIRECTIONAL):
     """One denoising step of one layer for one batch element (Alg. 2/5 -> Alg. 3 -> Alg. 1).
 
     States 0/1: k_in, v_in are the full-sequence K, V [Hkv, L, d]; the output is the block's
@@ -254,7 +269,7 @@ def block_step(step_in_block: int, delay: int, q_blk, k_in, v_in, cache, *, bloc
         out = dense_block_attention(q_blk, k_in, v_in, scale)
         if state == 1:
             idx, pooled, score = score_select(q_blk, k_in, block_off, block_len, r, s, score_mode,
-                                              select_mode, k_rounding, scale, pool_kind)
+                                              select_mode, k_rounding, scale, pool_kind, evict_scope)
             k_c, v_c = compact_kv(k_in, v_in, idx)
             cache.clear()
             cache.update(k=k_c, v=v_c, idx=idx, pooled=pooled, score=score)

@@ -1,0 +1,372 @@
+// C-ABI entry points: argument validation, launch planning and dispatch.  No arithmetic of the
+// method lives here except the retained-count rule and the cache-state schedule, which are host
+// logic by nature (Alg. 1 step 9; Alg. 2 / Alg. 5).
+#include <math.h>
+
+#include "../../include/sdllm.h"
+#include "sdllm_internal.h"
+
+using namespace sdllm;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline int elem_size(int dtype) { return dtype == SDLLM_BF16 ? 2 : 4; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int32_t quota(int32_t n, double r, int32_t rounding) {
+  const double x = r * (double)n;
+  const double k = rounding == SDLLM_CEIL ? ceil(x - 1e-9) : floor(x + 1e-9);
+  if (k < 0) return 0;
+  if (k > n) return n;
+  return (int32_t)k;
+}
+
+struct Counts { int32_t n_pre, n_suf, n_cand, k_total, k_pre, k_suf; };
+
+Counts counts_of(const sdllm_shape_t& s) {
+  Counts c;
+  c.n_pre = s.block_off;
+  c.n_suf = s.seq_len - s.block_off - s.block_len;
+  c.n_cand = c.n_pre + c.n_suf;
+  if (s.evict_scope == SDLLM_EVICT_PREFIX_ONLY) {
+    c.k_pre = quota(c.n_pre, s.retention, s.k_rounding);
+    c.k_suf = c.n_suf;
+    c.k_total = c.k_pre + c.k_suf;
+  } else if (s.select_mode == SDLLM_PER_SEGMENT) {
+    c.k_pre = quota(c.n_pre, s.retention, s.k_rounding);
+    c.k_suf = quota(c.n_suf, s.retention, s.k_rounding);
+    c.k_total = c.k_pre + c.k_suf;
+  } else {
+    c.k_total = quota(c.n_cand, s.retention, s.k_rounding);
+    c.k_pre = c.k_suf = -1;
+  }
+  return c;
+}
+
+bool strides_ok(const int64_t st[3], int esize) {
+  for (int i = 0; i < 3; ++i)
+    if (st[i] < 0 || (st[i] * esize) % 16 != 0) return false;
+  return true;
+}
+
+int32_t check_shape(const sdllm_shape_t* s) {
+  if (!s) return SDLLM_ERR_INVALID_ARG;
+  if (s->batch < 1 || s->n_kv_heads < 1 || s->n_q_heads < 1 || s->n_q_heads % s->n_kv_heads != 0)
+    return SDLLM_ERR_INVALID_ARG;
+  if (s->dtype != SDLLM_BF16 && s->dtype != SDLLM_F32) return SDLLM_ERR_INVALID_ARG;
+  if (s->block_len < 1 || s->block_off < 0 || s->seq_len < 1 ||
+      (int64_t)s->block_off + s->block_len > s->seq_len)
+    return SDLLM_ERR_INVALID_ARG;
+  if (!(s->retention >= 0.0 && s->retention <= 1.0)) return SDLLM_ERR_INVALID_ARG;
+  if (s->pool_kernel < 1 || s->pool_kernel % 2 == 0) return SDLLM_ERR_INVALID_ARG;
+  if (s->score_mode != SDLLM_SOFTMAX_MEAN && s->score_mode != SDLLM_LOGIT_MEAN) return SDLLM_ERR_INVALID_ARG;
+  if (s->select_mode != SDLLM_PER_SEGMENT && s->select_mode != SDLLM_JOINT) return SDLLM_ERR_INVALID_ARG;
+  if (s->k_rounding != SDLLM_CEIL && s->k_rounding != SDLLM_FLOOR) return SDLLM_ERR_INVALID_ARG;
+  if (s->pool_mode != SDLLM_MAX_POOL && s->pool_mode != SDLLM_AVG_POOL) return SDLLM_ERR_INVALID_ARG;
+  if (s->evict_scope != SDLLM_EVICT_BIDIRECTIONAL && s->evict_scope != SDLLM_EVICT_PREFIX_ONLY)
+    return SDLLM_ERR_INVALID_ARG;
+  if (!(s->softmax_scale >= 0.f) || !isfinite(s->softmax_scale) || s->reserved != 0) return SDLLM_ERR_INVALID_ARG;
+  const int es = elem_size(s->dtype);
+  if (!strides_ok(s->q_stride, es) || !strides_ok(s->kv_stride, es) || !strides_ok(s->blk_stride, es) ||
+      !strides_ok(s->cache_stride, es) || !strides_ok(s->out_stride, es))
+    return SDLLM_ERR_INVALID_ARG;
+  if (s->head_dim != 64 && s->head_dim != 128) return SDLLM_ERR_UNSUPPORTED;
+  if (s->block_len > 64) return SDLLM_ERR_UNSUPPORTED;
+  return SDLLM_OK;
+}
+
+bool row_stride_ok(const int64_t st[3], int d) { return st[2] >= d; }
+
+float scale_of(const sdllm_shape_t& s) {
+  return s.softmax_scale > 0.f ? s.softmax_scale : 1.0f / sqrtf((float)s.head_dim);
+}
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// ---------------------------------------------------------------- attention planning
+struct AttnPlan {
+  bool mfma;
+  int n_split, tiles_per_split, waves;
+  size_t part_o_bytes, part_ml_bytes;
+  size_t ws_bytes() const { return part_o_bytes + part_ml_bytes; }
+};
+
+bool seg_fits_u32(int64_t row_stride, int32_t n, int esize) {
+  return n <= 0 || ((int64_t)(n - 1) * row_stride + 128) * esize < (int64_t)1 << 31;
+}
+
+AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, int64_t sr1) {
+  AttnPlan pl{};
+  pl.mfma = s.dtype == SDLLM_BF16 && s.head_dim == 128 && s.block_len == 32 && seg_fits_u32(sr0, n0, 2) &&
+            seg_fits_u32(sr1, n1, 2);
+  pl.n_split = 1;
+  pl.tiles_per_split = 0;
+  pl.waves = 1;
+  if (pl.mfma) {
+    const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
+    const int heads = s.batch * s.n_q_heads;
+    // aim at 8 waves on every CU, never more waves than tiles
+    int waves_per_head = (kNumCUs * kMaxWavesPerWg + heads - 1) / heads;
+    if (waves_per_head > tiles) waves_per_head = tiles;
+    if (waves_per_head < 1) waves_per_head = 1;
+    pl.waves = waves_per_head < kMaxWavesPerWg ? waves_per_head : kMaxWavesPerWg;
+    int n_split = (waves_per_head + pl.waves - 1) / pl.waves;
+    pl.tiles_per_split = (tiles + n_split - 1) / n_split;
+    pl.n_split = (tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;   // no empty split
+    if (pl.n_split > 1) {
+      const size_t slots = (size_t)heads * pl.n_split;
+      pl.part_o_bytes = align_up(slots * s.block_len * s.head_dim * sizeof(float));
+      pl.part_ml_bytes = align_up(slots * 2 * s.block_len * sizeof(float));
+    }
+  }
+  return pl;
+}
+
+int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, const KvSegment& b, void* out, void* ws,
+                 size_t ws_bytes, hipStream_t stream) {
+  const AttnPlan pl = plan_attn(s, a.n, a.sr, b.n, b.sr);
+  if (pl.ws_bytes() > 0 && (!ws || ws_bytes < pl.ws_bytes())) return SDLLM_ERR_WORKSPACE;
+  AttnParams p{};
+  p.q = q;
+  p.out = out;
+  p.seg[0] = a;
+  p.seg[1] = b;
+  p.q_sb = s.q_stride[0]; p.q_sh = s.q_stride[1]; p.q_sr = s.q_stride[2];
+  p.o_sb = s.out_stride[0]; p.o_sh = s.out_stride[1]; p.o_sr = s.out_stride[2];
+  p.batch = s.batch; p.hq = s.n_q_heads; p.hkv = s.n_kv_heads; p.group = s.n_q_heads / s.n_kv_heads;
+  p.nq = s.block_len; p.d = s.head_dim;
+  p.scale_log2 = scale_of(s) * kLog2e;
+  p.n_split = pl.n_split; p.tiles_per_split = pl.tiles_per_split; p.waves = pl.waves;
+  p.part_o = (float*)ws;
+  p.part_ml = (float*)((char*)ws + pl.part_o_bytes);
+  hipError_t e;
+  if (pl.mfma) {
+    e = launch_attn_mfma_bf16(p, stream);
+    if (e == hipSuccess && pl.n_split > 1) e = launch_attn_combine(p, s.dtype, stream);
+  } else {
+    e = launch_attn_simple(p, s.dtype, stream);
+  }
+  return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
+}
+
+// ---------------------------------------------------------------- scoring planning
+struct ScorePlan {
+  int n_scored;       // candidates that get a score
+  size_t score_bytes, pooled_bytes, ml_bytes;
+  size_t ws_bytes() const { return score_bytes + pooled_bytes + ml_bytes; }
+};
+
+ScorePlan plan_score(const sdllm_shape_t& s) {
+  const Counts c = counts_of(s);
+  ScorePlan pl{};
+  pl.n_scored = s.evict_scope == SDLLM_EVICT_PREFIX_ONLY ? c.n_pre : c.n_cand;
+  const size_t rows = (size_t)s.batch * s.n_kv_heads;
+  pl.score_bytes = align_up(rows * c.n_cand * sizeof(float));
+  pl.pooled_bytes = pl.score_bytes;
+  pl.ml_bytes = align_up((size_t)s.batch * s.n_q_heads * 2 * s.block_len * sizeof(float));
+  return pl;
+}
+
+int32_t check_q(const sdllm_shape_t& s, const void* q) {
+  if (!q || !aligned16(q) || !row_stride_ok(s.q_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
+  return SDLLM_OK;
+}
+
+}  // namespace
+
+// ================================================================ exported functions
+extern "C" {
+
+const char* sdllm_error_string(int32_t status) {
+  switch (status) {
+    case SDLLM_OK: return "ok";
+    case SDLLM_ERR_INVALID_ARG: return "invalid argument";
+    case SDLLM_ERR_UNSUPPORTED: return "unsupported shape or type";
+    case SDLLM_ERR_WORKSPACE: return "workspace missing or too small";
+    case SDLLM_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int32_t sdllm_version(void) { return 100; }
+
+int32_t sdllm_retained_count(const sdllm_shape_t* shape, int32_t* k_total, int32_t* k_pre, int32_t* k_suf) {
+  const int32_t st = check_shape(shape);
+  if (st != SDLLM_OK) return st;
+  const Counts c = counts_of(*shape);
+  if (k_total) *k_total = c.k_total;
+  if (k_pre) *k_pre = c.k_pre;
+  if (k_suf) *k_suf = c.k_suf;
+  return SDLLM_OK;
+}
+
+int32_t sdllm_cache_state(int32_t step_in_block, int32_t delay, int32_t* state) {
+  if (!state || step_in_block < 0 || delay < 0) return SDLLM_ERR_INVALID_ARG;
+  *state = step_in_block > delay ? SDLLM_STATE_REUSE : (step_in_block == delay ? SDLLM_STATE_UPDATE : SDLLM_STATE_FULL);
+  return SDLLM_OK;
+}
+
+int32_t sdllm_workspace_bytes(const sdllm_shape_t* shape, int32_t op, int32_t n_cached, size_t* bytes) {
+  const int32_t st = check_shape(shape);
+  if (st != SDLLM_OK) return st;
+  if (!bytes) return SDLLM_ERR_INVALID_ARG;
+  const sdllm_shape_t& s = *shape;
+  size_t need = 0;
+  switch (op) {
+    case SDLLM_OP_SCORE_SELECT: need = plan_score(s).ws_bytes(); break;
+    case SDLLM_OP_COMPACT_KV: need = 0; break;
+    case SDLLM_OP_SPARSE_ATTN:
+      if (n_cached < 0) return SDLLM_ERR_INVALID_ARG;
+      need = plan_attn(s, n_cached, s.cache_stride[2], s.block_len, s.blk_stride[2]).ws_bytes();
+      break;
+    case SDLLM_OP_BLOCK_STEP: {
+      const Counts c = counts_of(s);
+      const size_t a = plan_attn(s, s.seq_len, s.kv_stride[2], 0, 0).ws_bytes();
+      const size_t b = plan_attn(s, c.k_total, s.cache_stride[2], s.block_len, s.blk_stride[2]).ws_bytes();
+      const size_t d = plan_score(s).ws_bytes();
+      need = a > b ? a : b;
+      need = need > d ? need : d;
+      break;
+    }
+    default: return SDLLM_ERR_INVALID_ARG;
+  }
+  *bytes = need > 0 ? need : kAlign;   // never zero, so callers can always allocate
+  return SDLLM_OK;
+}
+
+int32_t sdllm_score_select(const sdllm_shape_t* shape, const void* q_blk, const void* k_full, int32_t* idx_out,
+                           float* pooled_out, float* score_out, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_shape(shape);
+  if (st != SDLLM_OK) return st;
+  const sdllm_shape_t& s = *shape;
+  if ((st = check_q(s, q_blk)) != SDLLM_OK) return st;
+  if (!k_full || !aligned16(k_full) || !row_stride_ok(s.kv_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
+  const Counts c = counts_of(s);
+  if (c.k_total > 0 && !idx_out) return SDLLM_ERR_INVALID_ARG;
+  const ScorePlan pl = plan_score(s);
+  if (!ws || ws_bytes < pl.ws_bytes() || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return SDLLM_ERR_WORKSPACE;
+  if (c.n_cand == 0) return SDLLM_OK;
+  hipStream_t hs = (hipStream_t)stream;
+
+  float* score = score_out ? score_out : (float*)ws;
+  float* pooled = pooled_out ? pooled_out : (float*)((char*)ws + pl.score_bytes);
+  float* ml = (float*)((char*)ws + pl.score_bytes + pl.pooled_bytes);
+
+  ScoreParams sp{};
+  sp.q = q_blk; sp.k = k_full;
+  sp.q_sb = s.q_stride[0]; sp.q_sh = s.q_stride[1]; sp.q_sr = s.q_stride[2];
+  sp.k_sb = s.kv_stride[0]; sp.k_sh = s.kv_stride[1]; sp.k_sr = s.kv_stride[2];
+  sp.batch = s.batch; sp.hq = s.n_q_heads; sp.hkv = s.n_kv_heads; sp.group = s.n_q_heads / s.n_kv_heads;
+  sp.nq = s.block_len; sp.d = s.head_dim;
+  sp.block_off = s.block_off; sp.block_len = s.block_len;
+  sp.n_cand = pl.n_scored;
+  sp.score_stride = c.n_cand;
+  sp.softmax = s.score_mode == SDLLM_SOFTMAX_MEAN;
+  sp.scale = scale_of(s);
+  sp.scale_log2 = sp.scale * kLog2e;
+  sp.score = score;
+  sp.n_part = 1; sp.tiles_per_part = 0; sp.part_ml = ml; sp.waves = 1;
+  hipError_t e = launch_score_simple(sp, s.dtype, hs);
+  if (e != hipSuccess) return SDLLM_ERR_HIP;
+
+  SelectParams q{};
+  q.score = score; q.pooled = pooled; q.idx = idx_out;
+  q.rows = s.batch * s.n_kv_heads;
+  q.n_cand = c.n_cand;
+  q.k_total = c.k_total;
+  q.pool_half = (s.pool_kernel - 1) / 2;
+  q.avg_pool = s.pool_mode == SDLLM_AVG_POOL;
+  q.block_off = s.block_off; q.block_len = s.block_len;
+  if (s.evict_scope == SDLLM_EVICT_PREFIX_ONLY) {
+    q.n_seg = 1;
+    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
+    q.tail_begin = c.n_pre; q.tail_len = c.n_suf; q.tail_out = c.k_pre;
+  } else if (s.select_mode == SDLLM_PER_SEGMENT) {
+    q.n_seg = 2;
+    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
+    q.seg_begin[1] = c.n_pre; q.seg_len[1] = c.n_suf; q.seg_k[1] = c.k_suf; q.seg_out[1] = c.k_pre;
+  } else {
+    q.n_seg = 1;
+    q.seg_begin[0] = 0; q.seg_len[0] = c.n_cand; q.seg_k[0] = c.k_total; q.seg_out[0] = 0;
+  }
+  e = launch_select(q, hs);
+  return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
+}
+
+int32_t sdllm_compact_kv(const sdllm_shape_t* shape, const void* k_full, const void* v_full, const int32_t* idx,
+                         void* k_cache, void* v_cache, void* stream) {
+  const int32_t st = check_shape(shape);
+  if (st != SDLLM_OK) return st;
+  const sdllm_shape_t& s = *shape;
+  const Counts c = counts_of(s);
+  if (c.k_total == 0) return SDLLM_OK;
+  if (!k_full || !v_full || !idx || !k_cache || !v_cache) return SDLLM_ERR_INVALID_ARG;
+  if (!aligned16(k_full) || !aligned16(v_full) || !aligned16(k_cache) || !aligned16(v_cache))
+    return SDLLM_ERR_INVALID_ARG;
+  if (!row_stride_ok(s.kv_stride, s.head_dim) || !row_stride_ok(s.cache_stride, s.head_dim))
+    return SDLLM_ERR_INVALID_ARG;
+  const int es = elem_size(s.dtype);
+  CompactParams p{};
+  p.k = k_full; p.v = v_full; p.idx = idx; p.kc = k_cache; p.vc = v_cache;
+  p.s_sb = s.kv_stride[0] * es; p.s_sh = s.kv_stride[1] * es; p.s_sr = s.kv_stride[2] * es;
+  p.c_sb = s.cache_stride[0] * es; p.c_sh = s.cache_stride[1] * es; p.c_sr = s.cache_stride[2] * es;
+  p.batch = s.batch; p.hkv = s.n_kv_heads; p.k_total = c.k_total; p.seq_len = s.seq_len;
+  p.row_bytes = s.head_dim * es;
+  return launch_compact(p, (hipStream_t)stream) == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
+}
+
+int32_t sdllm_sparse_attn(const sdllm_shape_t* shape, const void* q_blk, const void* k_cache, const void* v_cache,
+                          int32_t n_cached, const void* k_blk, const void* v_blk, void* out, void* ws,
+                          size_t ws_bytes, void* stream) {
+  int32_t st = check_shape(shape);
+  if (st != SDLLM_OK) return st;
+  const sdllm_shape_t& s = *shape;
+  if ((st = check_q(s, q_blk)) != SDLLM_OK) return st;
+  if (n_cached < 0) return SDLLM_ERR_INVALID_ARG;
+  if (n_cached > 0 && (!k_cache || !v_cache || !aligned16(k_cache) || !aligned16(v_cache) ||
+                       !row_stride_ok(s.cache_stride, s.head_dim)))
+    return SDLLM_ERR_INVALID_ARG;
+  if (!k_blk || !v_blk || !out || !aligned16(k_blk) || !aligned16(v_blk) || !aligned16(out) ||
+      !row_stride_ok(s.blk_stride, s.head_dim) || !row_stride_ok(s.out_stride, s.head_dim))
+    return SDLLM_ERR_INVALID_ARG;
+  KvSegment a{k_cache, v_cache, s.cache_stride[0], s.cache_stride[1], s.cache_stride[2], n_cached};
+  KvSegment b{k_blk, v_blk, s.blk_stride[0], s.blk_stride[1], s.blk_stride[2], s.block_len};
+  return run_attn(s, q_blk, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int32_t delay, const void* q_blk,
+                         const void* k_in, const void* v_in, int32_t* idx, void* k_cache, void* v_cache, void* out,
+                         void* ws, size_t ws_bytes, void* stream, int32_t* state_out) {
+  int32_t st = check_shape(shape);
+  if (st != SDLLM_OK) return st;
+  const sdllm_shape_t& s = *shape;
+  int32_t state;
+  if ((st = sdllm_cache_state(step_in_block, delay, &state)) != SDLLM_OK) return st;
+  size_t need;
+  if ((st = sdllm_workspace_bytes(shape, SDLLM_OP_BLOCK_STEP, 0, &need)) != SDLLM_OK) return st;
+  if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return SDLLM_ERR_WORKSPACE;
+  if ((st = check_q(s, q_blk)) != SDLLM_OK) return st;
+  if (!k_in || !v_in || !out || !aligned16(k_in) || !aligned16(v_in) || !aligned16(out) ||
+      !row_stride_ok(s.out_stride, s.head_dim))
+    return SDLLM_ERR_INVALID_ARG;
+  const Counts c = counts_of(s);
+  if (state_out) *state_out = state;
+
+  if (state == SDLLM_STATE_REUSE) {
+    return sdllm_sparse_attn(shape, q_blk, k_cache, v_cache, c.k_total, k_in, v_in, out, ws, ws_bytes, stream);
+  }
+  // states 0/1: the block's rows of dense attention over all L keys of this step
+  if (!row_stride_ok(s.kv_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
+  if (state == SDLLM_STATE_UPDATE && c.k_total > 0 && (!idx || !k_cache || !v_cache)) return SDLLM_ERR_INVALID_ARG;
+  KvSegment a{k_in, v_in, s.kv_stride[0], s.kv_stride[1], s.kv_stride[2], s.seq_len};
+  KvSegment b{nullptr, nullptr, 0, 0, 0, 0};
+  st = run_attn(s, q_blk, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+  if (st != SDLLM_OK || state == SDLLM_STATE_FULL) return st;
+  st = sdllm_score_select(shape, q_blk, k_in, idx, nullptr, nullptr, ws, ws_bytes, stream);
+  if (st != SDLLM_OK) return st;
+  return sdllm_compact_kv(shape, k_in, v_in, idx, k_cache, v_cache, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,303 @@
+// Block-query attention over Concat(cache, block) for bf16, head_dim 128, 32 query rows
+// (Alg. 3 of the paper, cache_state == 2; the same kernel run over the full sequence is the
+// dense block-row attention of cache states 0 and 1).
+//
+// Design for gfx950.  The 32 query rows of one head make exactly one 32x32 MFMA block, so a
+// wavefront owns whole 32-key tiles: logits^T = K_tile * Q^T (K rows as the A operand, so each
+// lane ends up holding 16 logits of ONE query row and the softmax row reduction stays in
+// registers), then O^T += V_tile^T * P^T.  With 32 queries per 8 KB of K the kernel is bound by
+// HBM (about 31 flop/byte), so the structure is chosen for bytes in flight, not for MFMA rate:
+//   * each wave streams its own tiles; there is no workgroup barrier in the main loop;
+//   * global loads are full-row coalesced (16 lanes x 16 B per 256-byte row), held in registers
+//     for one tile of look-ahead, then written to a wave-private, row-padded LDS tile from
+//     which the MFMA operand fragments are read without bank conflicts;
+//   * V is read from LDS as 8-byte pieces of four head-dim columns and regrouped with v_perm so
+//     that four MFMAs cover all 128 columns (lane m of MFMA e produces column 4m+e);
+//   * up to 8 waves per workgroup split the keys of one head and merge their running
+//     (max, sum, numerator) through LDS; more workgroups per head (split-KV) write fp32
+//     partials that a small combine kernel merges.
+#include "sdllm_internal.h"
+
+namespace sdllm {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+// native vectors (not the HIP uint4 struct) so that register arrays of them are promoted to VGPRs
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kRowBytes = 256 + 16;               // 128 bf16 + one 16-byte pad: rows rotate over the banks
+constexpr int kTileBytes = kTileKeys * kRowBytes; // one 32 x 128 bf16 tile
+constexpr int kWaveLds = 2 * kTileBytes + 512;    // K tile, V tile, (max, sum) exchange
+
+size_t attn_mfma_lds_bytes(int waves) { return (size_t)waves * kWaveLds; }
+
+__device__ __forceinline__ uint32_t tile_off(int row, int chunk) {
+  // padded rows: the sixteen lanes that read one chunk column of sixteen rows hit sixteen different
+  // 16-byte bank groups, and every address is a per-lane base plus a compile-time constant
+  return (uint32_t)(row * kRowBytes + (chunk << 4));
+}
+
+// Tiles never straddle the two key segments: segment 0 contributes ceil(n0/32) tiles, segment 1
+// the rest.  A tile therefore has one wave-uniform base pointer and row count, and K and V (which
+// share strides) are addressed with the same eight per-lane 32-bit byte offsets.
+struct TileSrc {
+  const char* k;
+  const char* v;
+  int rows;        // valid keys in this tile (1..32)
+};
+
+struct SegPtrs {
+  const char* k0; const char* v0; uint32_t r0;   // byte stride per row, segment 0
+  const char* k1; const char* v1; uint32_t r1;
+  int n0, n1, tiles0;
+};
+
+__device__ __forceinline__ TileSrc tile_src(const SegPtrs& sp, int tile, uint32_t& row_stride) {
+  TileSrc ts;
+  if (tile < sp.tiles0) {
+    const int first = tile * kTileKeys;
+    ts.k = sp.k0 + (size_t)first * sp.r0;
+    ts.v = sp.v0 + (size_t)first * sp.r0;
+    ts.rows = min(kTileKeys, sp.n0 - first);
+    row_stride = sp.r0;
+  } else {
+    const int first = (tile - sp.tiles0) * kTileKeys;
+    ts.k = sp.k1 + (size_t)first * sp.r1;
+    ts.v = sp.v1 + (size_t)first * sp.r1;
+    ts.rows = min(kTileKeys, sp.n1 - first);
+    row_stride = sp.r1;
+  }
+  return ts;
+}
+
+__device__ __forceinline__ void load_tile(const SegPtrs& sp, int tile, int lane, u32x4 (&kreg)[8], u32x4 (&vreg)[8]) {
+  uint32_t stride;
+  const TileSrc ts = tile_src(sp, tile, stride);
+  const uint32_t c16 = (lane & 15) << 4;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    int r = j * 4 + (lane >> 4);
+    r = r < ts.rows ? r : ts.rows - 1;           // rows past the end re-read the last key; masked later
+    const uint32_t off = (uint32_t)r * stride + c16;
+    kreg[j] = *reinterpret_cast<const u32x4*>(ts.k + off);
+    vreg[j] = *reinterpret_cast<const u32x4*>(ts.v + off);
+  }
+}
+
+__global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nw = blockDim.x >> 6;
+  const int half = lane >> 5;
+  const int col = lane & 31;
+
+  // Consecutive workgroup ids go round-robin over the 8 XCDs; renumber so that the workgroups of
+  // one KV group (its query heads and key splits) sit on one XCD and share that XCD's L2.
+  int wg = blockIdx.x;
+  const int nwg = gridDim.x;
+  if ((nwg & (kNumXCDs - 1)) == 0) wg = (wg & (kNumXCDs - 1)) * (nwg / kNumXCDs) + wg / kNumXCDs;
+  const int split = wg % p.n_split;
+  const int head = wg / p.n_split;
+  const int b = head / p.hq;
+  const int h = head - b * p.hq;
+  const int g = h / p.group;
+
+  SegPtrs sp;
+  sp.n0 = p.seg[0].n;
+  sp.n1 = p.seg[1].n;
+  sp.tiles0 = (sp.n0 + kTileKeys - 1) / kTileKeys;
+  sp.r0 = (uint32_t)(p.seg[0].sr * 2);
+  sp.r1 = (uint32_t)(p.seg[1].sr * 2);
+  sp.k0 = (const char*)p.seg[0].k + 2 * (b * p.seg[0].sb + g * p.seg[0].sh);
+  sp.v0 = (const char*)p.seg[0].v + 2 * (b * p.seg[0].sb + g * p.seg[0].sh);
+  sp.k1 = (const char*)p.seg[1].k + 2 * (b * p.seg[1].sb + g * p.seg[1].sh);
+  sp.v1 = (const char*)p.seg[1].v + 2 * (b * p.seg[1].sb + g * p.seg[1].sh);
+  const int ntiles = sp.tiles0 + (sp.n1 + kTileKeys - 1) / kTileKeys;
+  const int t_begin = split * p.tiles_per_split;
+  const int t_end = min(ntiles, t_begin + p.tiles_per_split);
+
+  // Q^T fragments (B operand): lane (col = query row, half) holds head-dim [16t + 8 half, +8)
+  bf16x8 qf[8];
+  {
+    const u32x4* qp = reinterpret_cast<const u32x4*>((const char*)p.q + 2 * (b * p.q_sb + h * p.q_sh + col * p.q_sr));
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      u32x4 raw = qp[t * 2 + half];
+      qf[t] = __builtin_bit_cast(bf16x8, raw);
+    }
+  }
+
+  uint8_t* lds_k = smem + wave * kWaveLds;
+  uint8_t* lds_v = lds_k + kTileBytes;
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[e][i] = 0.f;
+  float m_run = -INFINITY;   // running row max (log2 domain), same in both halves
+  float l_run = 0.f;         // running row sum over the keys this half-lane has seen
+
+  u32x4 kreg[8], vreg[8];
+  int t = t_begin + wave;
+  if (t < t_end) load_tile(sp, t, lane, kreg, vreg);
+
+  for (; t < t_end; t += nw) {
+    // registers -> wave-private LDS tile
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t off = tile_off(j * 4 + (lane >> 4), lane & 15);
+      *reinterpret_cast<u32x4*>(lds_k + off) = kreg[j];
+      *reinterpret_cast<u32x4*>(lds_v + off) = vreg[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // next tile's loads fly while this one is computed
+    const int tn = t + nw;
+    if (tn < t_end) load_tile(sp, tn, lane, kreg, vreg);
+
+    // logits^T[key, query] = K_tile Q^T
+    f32x16 s;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(lds_k + tile_off(col, kk * 2 + half));
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s, 0, 0, 0);
+    }
+    // register i of this lane is key 8*(i/4) + 4*half + i%4 of the tile, query row `col`
+    const int key0 = half * 4;
+    const int rows = t < sp.tiles0 ? min(kTileKeys, sp.n0 - t * kTileKeys) : min(kTileKeys, sp.n1 - (t - sp.tiles0) * kTileKeys);
+    float m_loc = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key = key0 + (i >> 2) * 8 + (i & 3);
+      s[i] = key < rows ? s[i] * p.scale_log2 : -INFINITY;
+      m_loc = fmaxf(m_loc, s[i]);
+    }
+    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
+    const float m_new = fmaxf(m_run, m_loc);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float l_loc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      s[i] = __builtin_amdgcn_exp2f(s[i] - m_new);
+      l_loc += s[i];
+    }
+    l_run = l_run * alpha + l_loc;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[e][i] *= alpha;
+
+    // O^T[col 4m+e, query] += V_tile^T P^T, 16 keys per MFMA step
+#pragma unroll
+    for (int step = 0; step < 2; ++step) {
+      bf16x8 pb;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pb[j] = (__bf16)s[step * 8 + j];
+      u32x2 vv[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int key_local = step * 16 + (j >> 2) * 8 + half * 4 + (j & 3);
+        vv[j] = *reinterpret_cast<const u32x2*>(lds_v + tile_off(key_local, col >> 1) + ((col & 1) << 3));
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        u32x4 w;
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        w.x = __builtin_amdgcn_perm(e < 2 ? vv[1].x : vv[1].y, e < 2 ? vv[0].x : vv[0].y, sel);
+        w.y = __builtin_amdgcn_perm(e < 2 ? vv[3].x : vv[3].y, e < 2 ? vv[2].x : vv[2].y, sel);
+        w.z = __builtin_amdgcn_perm(e < 2 ? vv[5].x : vv[5].y, e < 2 ? vv[4].x : vv[4].y, sel);
+        w.w = __builtin_amdgcn_perm(e < 2 ? vv[7].x : vv[7].y, e < 2 ? vv[6].x : vv[6].y, sel);
+        acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pb, acc[e], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+
+  float l_tot = l_run + __shfl_xor(l_run, 32);
+
+  // merge the waves of this workgroup: waves 1.. park their state in their own LDS region
+  if (nw > 1) {
+    float* my_acc = reinterpret_cast<float*>(smem + wave * kWaveLds);
+    float* my_ml = my_acc + 4096;
+    if (wave > 0) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) my_acc[(e * 16 + i) * 64 + lane] = acc[e][i];
+      if (lane < 32) { my_ml[lane] = m_run; my_ml[32 + lane] = l_tot; }
+    }
+    __syncthreads();
+    if (wave > 0) return;
+    for (int w = 1; w < nw; ++w) {
+      const float* o_acc = reinterpret_cast<const float*>(smem + w * kWaveLds);
+      const float* o_ml = o_acc + 4096;
+      const float m_o = o_ml[col];
+      const float l_o = o_ml[32 + col];
+      const float m_new = fmaxf(m_run, m_o);
+      // a wave that saw no tile carries (-inf, 0, 0): its factor is 0 whenever m_new is finite
+      const float f_me = m_run == m_new ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+      const float f_o = m_o == m_new ? 1.f : __builtin_amdgcn_exp2f(m_o - m_new);
+      l_tot = l_tot * f_me + l_o * f_o;
+      m_run = m_new;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[e][i] = acc[e][i] * f_me + o_acc[(e * 16 + i) * 64 + lane] * f_o;
+    }
+  }
+
+  if (p.n_split == 1) {
+    const float inv = 1.f / l_tot;
+    char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
+      bf16x4 o4;
+      o4[0] = (__bf16)(acc[0][i] * inv);
+      o4[1] = (__bf16)(acc[1][i] * inv);
+      o4[2] = (__bf16)(acc[2][i] * inv);
+      o4[3] = (__bf16)(acc[3][i] * inv);
+      *reinterpret_cast<bf16x4*>(op + mrow * 8) = o4;
+    }
+  } else {
+    const size_t slot = (size_t)head * p.n_split + split;
+    float* po = p.part_o + (slot * 32 + col) * 128;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
+      f32x4 o4 = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+      *reinterpret_cast<f32x4*>(po + mrow * 4) = o4;
+    }
+    if (lane < 32) {
+      p.part_ml[slot * 64 + lane] = m_run;
+      p.part_ml[slot * 64 + 32 + lane] = l_tot;
+    }
+  }
+}
+
+hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s) {
+  const int nwg = p.batch * p.hq * p.n_split;
+  const size_t lds = attn_mfma_lds_bytes(p.waves);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(kMaxWavesPerWg));
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(attn_mfma_bf16_kernel, dim3(nwg), dim3(p.waves * kWave), lds, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace sdllm

@@ -1,0 +1,102 @@
+// Internal declarations shared by the C-ABI dispatcher and the kernel launchers.
+// Nothing here is exported; the public surface is include/sdllm.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sdllm {
+
+constexpr int kWave = 64;            // CDNA wavefront
+constexpr int kTileKeys = 32;        // keys per MFMA tile (one 32x32 block of logits)
+constexpr int kMaxWavesPerWg = 8;    // attention / scoring workgroups hold up to 8 waves
+constexpr int kNumCUs = 256;         // MI355X
+constexpr int kNumXCDs = 8;
+
+// One source of keys/values: rows of a [B, Hkv, n, d] tensor given by element strides.
+struct KvSegment {
+  const void* k;
+  const void* v;
+  int64_t sb, sh, sr;  // element strides: batch, head, row
+  int32_t n;           // rows per (batch, head)
+};
+
+// Attention of nq query rows per head over Concat(seg[0], seg[1]) (Alg. 3, state 2; with a
+// single full-sequence segment it is the dense block-row attention of states 0/1).
+struct AttnParams {
+  const void* q;
+  void* out;
+  KvSegment seg[2];
+  int64_t q_sb, q_sh, q_sr;
+  int64_t o_sb, o_sh, o_sr;
+  int32_t batch, hq, hkv, group, nq, d;
+  float scale_log2;     // softmax scale * log2(e)
+  // split-KV plan
+  int32_t n_split;          // workgroups per head
+  int32_t tiles_per_split;  // 32-key tiles each workgroup owns
+  int32_t waves;            // waves per workgroup
+  float* part_o;            // [B*Hq, n_split, nq, d] fp32 partial numerators (n_split > 1)
+  float* part_ml;           // [B*Hq, n_split, 2, nq] running max (log2 domain) and denominator
+};
+
+// Scoring of the candidates K_f = Concat[K_{:o}, K_{o+b:}] against the block's queries.
+struct ScoreParams {
+  const void* q;
+  const void* k;        // full-sequence keys
+  int64_t q_sb, q_sh, q_sr;
+  int64_t k_sb, k_sh, k_sr;
+  int32_t batch, hq, hkv, group, nq, d;
+  int32_t block_off, block_len;
+  int32_t n_cand;       // candidates scored (N, or N_pre for prefix-only eviction)
+  int32_t softmax;      // 1: SOFTMAX_MEAN, 0: LOGIT_MEAN
+  float scale;          // softmax scale
+  float scale_log2;     // scale * log2(e)
+  float* score;         // [B*Hkv, score_stride], the first n_cand of each row written
+  int32_t score_stride;
+  // row statistics of the softmax (pass 1 -> pass 2)
+  int32_t n_part;       // partial (max, sum) pairs per query row
+  int32_t tiles_per_part;
+  float* part_ml;       // [B*Hq, n_part, 2, nq]
+  int32_t waves;
+};
+
+struct SelectParams {
+  const float* score;   // [rows, n_cand]
+  float* pooled;        // [rows, n_cand]
+  int32_t* idx;         // [rows, k_total]
+  int32_t rows;         // B * Hkv
+  int32_t n_cand;
+  int32_t n_seg;        // 1 or 2 ranked segments
+  int32_t seg_begin[2], seg_len[2], seg_k[2], seg_out[2];
+  int32_t k_total;
+  int32_t pool_half;    // (s-1)/2
+  int32_t avg_pool;
+  int32_t block_off, block_len;
+  // candidates appended unconditionally after the ranked ones (prefix-only eviction keeps the
+  // whole suffix): candidate indices [tail_begin, tail_begin + tail_len)
+  int32_t tail_begin, tail_len, tail_out;
+};
+
+struct CompactParams {
+  const void* k;
+  const void* v;
+  const int32_t* idx;
+  void* kc;
+  void* vc;
+  int64_t s_sb, s_sh, s_sr;  // source strides in BYTES
+  int64_t c_sb, c_sh, c_sr;  // cache strides in BYTES
+  int32_t batch, hkv, k_total, seq_len;
+  int32_t row_bytes;
+};
+
+// kernel launchers (each returns hipGetLastError() after its launches)
+hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s);
+hipError_t launch_attn_simple(const AttnParams& p, int dtype, hipStream_t s);
+hipError_t launch_attn_combine(const AttnParams& p, int dtype, hipStream_t s);
+hipError_t launch_score_mfma_bf16(const ScoreParams& p, hipStream_t s);
+hipError_t launch_score_simple(const ScoreParams& p, int dtype, hipStream_t s);
+hipError_t launch_select(const SelectParams& p, hipStream_t s);
+hipError_t launch_compact(const CompactParams& p, hipStream_t s);
+
+}  // namespace sdllm

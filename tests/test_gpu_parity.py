@@ -1,0 +1,224 @@
+"""GPU-vs-oracle parity of the HIP path, element by element, through the C ABI.
+
+Index sets: bit-exact outside the tie band (entries whose oracle pooled score lies within 1e-4
+relative of the k-th value are reported as ties and may differ).  Compaction: bit-exact.
+Attention outputs: max-abs <= 2e-2 and mean-abs <= 2e-3 for bf16 tensors with fp32 accumulation,
+1e-5 / 1e-6 for fp32 tensors.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sdllm_oracle as orc
+from paper_2508_02558_amd import binding as B
+from paper_2508_02558_amd import workloads as wl
+from tests import parity_util as U
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _note(msg):
+    print(msg, flush=True)
+
+
+def _run_block(w, layer=0, block_index=0, n_steps=4, delay=1, **modes):
+    """A whole decoding block through sdllm_block_step against the oracle, every step."""
+    _note(f"[case] block_step workload={w.name} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} "
+          f"L={w.seq_len} block={block_index} modes={modes}")
+    inp = wl.make_block_inputs(w, layer, block_index, n_steps)
+    shape = U.shape_for(w, block_index, **modes)
+    o, b = inp["block_off"], w.block
+    gl = U.GpuLayer(shape, DEV)
+    k_full = inp["k_full"].to(DEV)
+    v_full = inp["v_full"].to(DEV)
+    q_all, kb_all, vb_all = inp["q"].to(DEV), inp["k_blk"].to(DEV), inp["v_blk"].to(DEV)
+    cache_gpu = None
+    ties = 0
+    for t in range(n_steps):
+        state = orc.cache_state(t, delay)
+        q = q_all[t].contiguous()
+        if state < 2:
+            k_full[:, :, o:o + b] = kb_all[t]
+            v_full[:, :, o:o + b] = vb_all[t]
+            st = gl.block_step(t, delay, q, k_full, v_full)
+            ref = U.oracle_attention_batch(q, k_full, v_full)
+            U.assert_close(gl.out, ref, w.dtype, f"dense step {t}")
+            if state == 1:
+                idx_gpu = gl.idx[:, :, :gl.k_total].cpu().numpy().astype(np.int64)
+                idx_orc, pooled_orc, _ = U.oracle_score_select(shape, q, k_full)
+                for bi in range(w.batch):
+                    for g in range(w.n_kv_heads):
+                        ties += U.compare_index_rows(idx_gpu[bi, g], idx_orc[bi, g], pooled_orc[bi, g], w.seq_len, o, b,
+                                                     U.ranked_segments(shape))
+                # compaction is a byte copy of the rows the GPU itself selected
+                ig = torch.from_numpy(idx_gpu).to(DEV)
+                want_k = torch.gather(k_full, 2, ig[..., None].expand(-1, -1, -1, w.head_dim))
+                want_v = torch.gather(v_full, 2, ig[..., None].expand(-1, -1, -1, w.head_dim))
+                assert torch.equal(gl.k_cache[:, :, :gl.k_total], want_k)
+                assert torch.equal(gl.v_cache[:, :, :gl.k_total], want_v)
+                cache_gpu = (want_k, want_v)
+        else:
+            kb, vb = kb_all[t].contiguous(), vb_all[t].contiguous()
+            st = gl.block_step(t, delay, q, kb, vb)
+            # end to end with the GPU's own index set (the oracle attends to the same rows)
+            ref = U.oracle_attention_batch(q, torch.cat([cache_gpu[0], kb], 2), torch.cat([cache_gpu[1], vb], 2))
+            U.assert_close(gl.out, ref, w.dtype, f"sparse step {t}")
+        assert st == state
+    _note(f"[done] ties in band: {ties}")
+    return ties
+
+
+def test_tiny_fp32_block():
+    _run_block(wl.WORKLOADS["tiny"])
+
+
+@pytest.mark.parametrize("modes", [
+    dict(score_mode=B.SDLLM_LOGIT_MEAN),
+    dict(select_mode=B.SDLLM_JOINT, k_rounding=B.SDLLM_FLOOR),
+    dict(select_mode=B.SDLLM_JOINT, score_mode=B.SDLLM_LOGIT_MEAN, k_rounding=B.SDLLM_FLOOR),
+    dict(pool_mode=B.SDLLM_AVG_POOL),
+    dict(evict_scope=B.SDLLM_EVICT_PREFIX_ONLY),
+])
+def test_tiny_fp32_modes(modes):
+    _run_block(wl.WORKLOADS["tiny"], n_steps=3, **modes)
+
+
+@pytest.mark.parametrize("delay", [0, 2, 3])
+def test_tiny_delay_sweep(delay):
+    _run_block(wl.WORKLOADS["tiny"].scaled(steps_per_block=6), n_steps=6, delay=delay)
+
+
+@pytest.mark.parametrize("r,s", [(0.1, 1), (0.3, 5), (0.7, 7), (0.9, 9), (0.0, 3), (1.0, 3)])
+def test_tiny_retention_and_kernel_sweep(r, s):
+    _run_block(wl.WORKLOADS["tiny"].scaled(retention=r, pool_kernel=s), n_steps=3)
+
+
+def test_llada_layer_bf16_block():
+    # the LLaDA-8B-shaped single layer at full size: 32 heads, prompt 1024, first block
+    _run_block(wl.WORKLOADS["llada8b_layer"], n_steps=3)
+
+
+def test_llada_layer_last_block_has_no_suffix():
+    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=4, n_kv_heads=4)
+    _run_block(w, block_index=w.n_blocks - 1, n_steps=3)
+
+
+def test_block_at_sequence_start_has_no_prefix():
+    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=4, n_kv_heads=4, prompt=0, gen=512)
+    _run_block(w, block_index=0, n_steps=3)
+
+
+def test_dream_gqa_bf16_block():
+    _run_block(wl.WORKLOADS["dream7b_gqa"], n_steps=3)
+
+
+def test_dream_gqa_modes():
+    w = wl.WORKLOADS["dream7b_gqa"].scaled(prompt=1000, gen=96)   # ragged: 1000 and 64 candidates per side
+    _run_block(w, n_steps=3, select_mode=B.SDLLM_JOINT, k_rounding=B.SDLLM_FLOOR)
+    _run_block(w, n_steps=3, score_mode=B.SDLLM_LOGIT_MEAN, evict_scope=B.SDLLM_EVICT_PREFIX_ONLY)
+
+
+def test_bf16_head_dim_64_and_short_block_take_the_generic_path():
+    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=4, n_kv_heads=2, head_dim=64, prompt=200, gen=64)
+    _run_block(w, n_steps=3)
+    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=2, n_kv_heads=2, prompt=100, gen=48, block=16)
+    _run_block(w, n_steps=3)
+
+
+def test_batched_block():
+    w = wl.WORKLOADS["llada8b_sweep"].scaled(batch=3, n_q_heads=4, n_kv_heads=4, prompt=300, gen=64)
+    _run_block(w, n_steps=3)
+
+
+# ------------------------------------------------------------------ sdllm_sparse_attn on its own
+@pytest.mark.parametrize("n_cached", [0, 1, 31, 32, 33, 77, 1000, 2165])
+def test_sparse_attn_ragged_cache_lengths(n_cached):
+    _note(f"[case] sparse_attn n_cached={n_cached}")
+    torch.manual_seed(n_cached)
+    Bt, Hq, Hkv, b, d = 2, 8, 4, 32, 128
+    shape = B.make_shape(batch=Bt, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, seq_len=4096, block_off=2048,
+                         block_len=b, dtype=B.SDLLM_BF16, cache_rows=max(1, n_cached))
+    q = torch.randn(Bt, Hq, b, d, device=DEV).bfloat16()
+    kc = torch.randn(Bt, Hkv, max(1, n_cached), d, device=DEV).bfloat16()
+    vc = torch.randn_like(kc.float()).bfloat16()
+    kb = torch.randn(Bt, Hkv, b, d, device=DEV).bfloat16()
+    vb = torch.randn(Bt, Hkv, b, d, device=DEV).bfloat16()
+    out = torch.zeros(Bt, Hq, b, d, device=DEV, dtype=torch.bfloat16)
+    ws = torch.empty(B.sdllm_workspace_bytes(shape, B.SDLLM_OP_SPARSE_ATTN, n_cached), dtype=torch.uint8, device=DEV)
+    B.sdllm_sparse_attn(shape, q, kc if n_cached else None, vc if n_cached else None, n_cached, kb, vb, out, ws)
+    torch.cuda.synchronize()
+    ref = U.oracle_attention_batch(q, torch.cat([kc[:, :, :n_cached], kb], 2), torch.cat([vc[:, :, :n_cached], vb], 2))
+    U.assert_close(out, ref, "bf16", f"n_cached={n_cached}")
+
+
+def test_sparse_attn_strided_views_and_explicit_scale():
+    _note("[case] sparse_attn strided views")
+    torch.manual_seed(5)
+    Bt, Hq, Hkv, b, d, n = 2, 4, 2, 32, 128, 150
+    # tensors stored [B, n, H, d] and passed as [B, H, n, d] views
+    q = torch.randn(Bt, b, Hq, d, device=DEV).bfloat16().permute(0, 2, 1, 3)
+    kc = torch.randn(Bt, 200, Hkv, d, device=DEV).bfloat16().permute(0, 2, 1, 3)
+    vc = torch.randn(Bt, 200, Hkv, d, device=DEV).bfloat16().permute(0, 2, 1, 3)
+    kb = torch.randn(Bt, b, Hkv, d, device=DEV).bfloat16().permute(0, 2, 1, 3)
+    vb = torch.randn(Bt, b, Hkv, d, device=DEV).bfloat16().permute(0, 2, 1, 3)
+    out = torch.zeros(Bt, b, Hq, d, device=DEV, dtype=torch.bfloat16).permute(0, 2, 1, 3)
+    shape = B.make_shape(batch=Bt, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, seq_len=1024, block_off=512, block_len=b,
+                         dtype=B.SDLLM_BF16, softmax_scale=0.05, q_stride=B.strides_of(q),
+                         cache_stride=B.strides_of(kc), blk_stride=B.strides_of(kb), out_stride=B.strides_of(out))
+    ws = torch.empty(B.sdllm_workspace_bytes(shape, B.SDLLM_OP_SPARSE_ATTN, n), dtype=torch.uint8, device=DEV)
+    B.sdllm_sparse_attn(shape, q, kc, vc, n, kb, vb, out, ws)
+    torch.cuda.synchronize()
+    ref = U.oracle_attention_batch(q, torch.cat([kc[:, :, :n], kb], 2), torch.cat([vc[:, :, :n], vb], 2), scale=0.05)
+    U.assert_close(out, ref, "bf16", "strided")
+
+
+def test_r_one_reproduces_dense_attention_and_zero_queries_pick_lowest_positions():
+    _note("[case] r=1 and all-ties")
+    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=4, n_kv_heads=4, prompt=256, gen=96, retention=1.0)
+    inp = wl.make_block_inputs(w, n_steps=2)
+    shape = U.shape_for(w)
+    gl = U.GpuLayer(shape, DEV)
+    q = inp["q"][1].to(DEV).contiguous()
+    k, v = inp["k_full"].to(DEV), inp["v_full"].to(DEV)
+    o, b = inp["block_off"], w.block
+    idx, _, _ = gl.score_select(q, k)
+    cand = orc.candidate_positions(w.seq_len, o, b)
+    assert (idx == cand[None, None]).all()
+    gl.compact(k, v)
+    out = gl.sparse_attn(q, k[:, :, o:o + b].contiguous(), v[:, :, o:o + b].contiguous()).clone()
+    gl.block_step(0, 1, q, k, v)   # dense
+    assert (out.float() - gl.out.float()).abs().max().item() <= 2e-2
+    U.assert_close(out, U.oracle_attention_batch(q, k, v), "bf16", "r=1 sparse == dense")
+    # all-zero queries: every candidate ties, the lowest positions of each segment win
+    w2 = w.scaled(retention=0.5)
+    shape2 = U.shape_for(w2)
+    gl2 = U.GpuLayer(shape2, DEV)
+    idx2, pooled2, score2 = gl2.score_select(torch.zeros_like(q), k)
+    n_pre, n_suf = o, w.seq_len - o - b
+    want = np.concatenate([np.arange(n_pre // 2), o + b + np.arange(n_suf // 2)])
+    assert (idx2 == want[None, None]).all()
+    np.testing.assert_allclose(score2.cpu().numpy(), 1.0 / (n_pre + n_suf), rtol=1e-5)
+
+
+def test_scores_match_oracle_values():
+    _note("[case] score / pooled values")
+    for name, kw in (("llada8b_layer", dict(n_q_heads=4, n_kv_heads=4, prompt=500, gen=128)),
+                     ("dream7b_gqa", dict(prompt=700, gen=96)), ("tiny", {})):
+        w = wl.WORKLOADS[name].scaled(**kw)
+        inp = wl.make_block_inputs(w, n_steps=2)
+        for mode in (B.SDLLM_SOFTMAX_MEAN, B.SDLLM_LOGIT_MEAN):
+            shape = U.shape_for(w, score_mode=mode)
+            gl = U.GpuLayer(shape, DEV)
+            q = inp["q"][1].to(DEV).contiguous()
+            k = inp["k_full"].to(DEV)
+            _, pooled, score = gl.score_select(q, k)
+            _, pooled_orc, score_orc = U.oracle_score_select(shape, q, k)
+            sg, pg = score.cpu().double().numpy(), pooled.cpu().double().numpy()
+            if mode == B.SDLLM_SOFTMAX_MEAN:
+                np.testing.assert_allclose(sg, score_orc, rtol=2e-5, atol=1e-12)
+                np.testing.assert_allclose(pg, pooled_orc, rtol=2e-5, atol=1e-12)
+                np.testing.assert_allclose(sg.sum(-1), 1.0, rtol=1e-5)
+            else:
+                np.testing.assert_allclose(sg, score_orc, rtol=0, atol=2e-5)
+                np.testing.assert_allclose(pg, pooled_orc, rtol=0, atol=2e-5)

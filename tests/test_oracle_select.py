@@ -174,3 +174,19 @@ def test_candidate_positions():
     assert orc.candidate_positions(10, 4, 2).tolist() == [0, 1, 2, 3, 6, 7, 8, 9]
     assert orc.candidate_positions(6, 0, 2).tolist() == [2, 3, 4, 5]
     assert orc.candidate_positions(6, 4, 2).tolist() == [0, 1, 2, 3]
+
+
+def test_prefix_only_eviction_keeps_the_whole_suffix():
+    """Alg. 4: the prefix is ranked exactly as a sequence that ends with the block would be, and every
+    suffix position is appended."""
+    rng = np.random.default_rng(21)
+    hq, hkv, b, d, L, o = 4, 2, 4, 8, 30, 12
+    q = rng.standard_normal((hq, b, d)); k = rng.standard_normal((hkv, L, d))
+    idx, pooled, score = orc.score_select(q, k, o, b, 0.5, 3, evict_scope=orc.PREFIX_ONLY)
+    ref, pooled_ref, _ = orc.score_select(q, k[:, :o + b], o, b, 0.5, 3)
+    assert pooled.shape == (hkv, o)
+    np.testing.assert_array_equal(pooled, pooled_ref)
+    for g in range(hkv):
+        assert idx[g].tolist() == ref[g].tolist() + list(range(o + b, L))
+        # the softmax is normalised over the prefix alone
+        np.testing.assert_allclose(score[g].sum(), 1.0, rtol=1e-13)
