@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the Sparse-dLLM hot path on one MI355X.
+
+A "step" is one decoding block of the whole workload: every layer runs the 32 denoising steps of
+one block through sdllm_block_step (1 dense step, 1 dense + score/select/compact step, 30 sparse
+steps at the paper's settings), in model order (for each denoising step, every layer).  All inputs
+are synthetic, generated on the device before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llada8b_sweep] [--layers N]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E
+
+
+def attn_bytes(batch, hq, hkv, d, n_keys, nq, esize):
+    """Algorithmic bytes of one block-attention launch: K and V rows read once, Q in, O out."""
+    return 2 * batch * hkv * n_keys * d * esize + 2 * batch * hq * nq * d * esize
+
+
+def cpu_baseline(w, inp0, n_batch, threads_note):
+    """The float64 oracle on one layer's block, `n_batch` batch elements, all 32 steps."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle import sdllm_oracle as orc
+    from paper_2508_02558_amd import workloads as wl
+
+    o, b = inp0["block_off"], w.block
+    t0 = time.perf_counter()
+    for bi in range(n_batch):
+        k_full = wl.to_f64(inp0["k_full"][bi])
+        v_full = wl.to_f64(inp0["v_full"][bi])
+        cache = {}
+        for t in range(w.steps_per_block):
+            q = wl.to_f64(inp0["q"][t, bi])
+            if orc.cache_state(t, 1) < 2:
+                orc.block_step(t, 1, q, k_full, v_full, cache, block_off=o, block_len=b, r=w.retention, s=w.pool_kernel)
+            else:
+                orc.block_step(t, 1, q, wl.to_f64(inp0["k_blk"][t, bi]), wl.to_f64(inp0["v_blk"][t, bi]), cache,
+                               block_off=o, block_len=b, r=w.retention, s=w.pool_kernel)
+    dt = time.perf_counter() - t0
+    # one sdllm_block_step call covers the whole batch of one layer for one denoising step
+    calls_equiv = w.steps_per_block * n_batch / w.batch
+    blas = [p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"]
+    return {
+        "value": calls_equiv / dt, "unit": "block-steps/s per layer", "cores": max(blas) if blas else 1,
+        "kind": "oracle",
+        "sample": f"one layer, {n_batch} of {w.batch} batch elements, all {w.steps_per_block} denoising steps of one "
+                  f"block ({dt:.1f} s of CPU work), scaled to the full batch",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llada8b_sweep")
+    ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-batch", type=int, default=8, help="batch elements the oracle baseline runs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2508_02558_amd import binding as B
+    from paper_2508_02558_amd import workloads as wl
+
+    B.load()   # fails loudly when the HIP library has not been built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    w = wl.WORKLOADS[args.workload]
+    n_layers = args.layers if args.layers > 0 else w.n_layers
+    # one-layer workloads are rotated over 32 distinct buffer sets so that re-reads cannot be
+    # served by the 256 MB last-level cache
+    if n_layers == 1 and args.layers == 0:
+        n_layers = 32
+    T = w.steps_per_block
+    o, b = w.block_off(0), w.block
+    esize = 2 if w.dtype == "bf16" else 4
+    shape = B.make_shape(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                         seq_len=w.seq_len, block_off=o, block_len=b,
+                         dtype=B.SDLLM_BF16 if w.dtype == "bf16" else B.SDLLM_F32, retention=w.retention,
+                         pool_kernel=w.pool_kernel)
+    k_total, _, _ = B.sdllm_retained_count(shape)
+    shape = B.make_shape(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                         seq_len=w.seq_len, block_off=o, block_len=b,
+                         dtype=B.SDLLM_BF16 if w.dtype == "bf16" else B.SDLLM_F32, retention=w.retention,
+                         pool_kernel=w.pool_kernel, cache_rows=max(1, k_total))
+    ws = torch.empty(B.sdllm_workspace_bytes(shape, B.SDLLM_OP_BLOCK_STEP), dtype=torch.uint8, device=dev)
+
+    layers = []
+    inp0_host = None
+    for layer in range(n_layers):
+        inp = wl.make_block_inputs(w, layer, 0, T, device=dev)
+        td = w.torch_dtype
+        st = dict(k_full=inp["k_full"], v_full=inp["v_full"], q=inp["q"], k_blk=inp["k_blk"], v_blk=inp["v_blk"],
+                  k_cache=torch.zeros(w.batch, w.n_kv_heads, max(1, k_total), w.head_dim, dtype=td, device=dev),
+                  v_cache=torch.zeros(w.batch, w.n_kv_heads, max(1, k_total), w.head_dim, dtype=td, device=dev),
+                  idx=torch.zeros(w.batch, w.n_kv_heads, max(1, k_total), dtype=torch.int32, device=dev),
+                  out=torch.zeros(w.batch, w.n_q_heads, b, w.head_dim, dtype=td, device=dev))
+        layers.append(st)
+        if layer == 0 and not args.no_cpu_baseline:
+            nb = min(args.cpu_batch, w.batch)
+            inp0_host = {k: (v[:nb].cpu() if k in ("k_full", "v_full") else v[:, :nb].cpu())
+                         for k, v in inp.items() if k in ("k_full", "v_full", "q", "k_blk", "v_blk")}
+            inp0_host["block_off"] = o
+    torch.cuda.synchronize()
+
+    states = [B.sdllm_cache_state(t, 1) for t in range(T)]
+    sparse_events = []   # (start, stop) around every all-layer sweep of sparse (state-2) calls
+
+    def run_block(record: bool):
+        for t in range(T):
+            reuse = states[t] == B.SDLLM_STATE_REUSE
+            if record and reuse:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            for st in layers:
+                if reuse:
+                    B.sdllm_block_step(shape, t, 1, st["q"][t], st["k_blk"][t], st["v_blk"][t], st["idx"], st["k_cache"],
+                                       st["v_cache"], st["out"], ws)
+                else:
+                    # a model produces fresh full-sequence K/V at these steps; the synthetic driver
+                    # reuses the resident tensors (same bytes read)
+                    B.sdllm_block_step(shape, t, 1, st["q"][t], st["k_full"], st["v_full"], st["idx"], st["k_cache"],
+                                       st["v_cache"], st["out"], ws)
+            if record and reuse:
+                e1.record()
+                sparse_events.append((e0, e1))
+
+    for _ in range(args.warmup):
+        run_block(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_block(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    elapsed = t1 - t0
+    calls = args.steps * T * n_layers
+    sparse_ms = [a.elapsed_time(bb) for a, bb in sparse_events]
+    sparse_launch_us = 1e3 * sum(sparse_ms) / (len(sparse_ms) * n_layers) if sparse_ms else float("nan")
+    bytes_sparse = attn_bytes(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, k_total + b, b, esize)
+    achieved = bytes_sparse / (sparse_launch_us * 1e-6) / 1e9 if sparse_ms else float("nan")
+
+    # per-stage launch times outside the headline region (same buffers, event-timed sweeps over all layers)
+    def sweep_us(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return 1e3 * e0.elapsed_time(e1) / (reps * n_layers)
+
+    def dense_sweep():
+        for st in layers:
+            B.sdllm_block_step(shape, 0, 1, st["q"][0], st["k_full"], st["v_full"], st["idx"], st["k_cache"], st["v_cache"],
+                               st["out"], ws)
+
+    def score_sweep():
+        for st in layers:
+            B.sdllm_score_select(shape, st["q"][1], st["k_full"], st["idx"], None, None, ws)
+
+    def compact_sweep():
+        for st in layers:
+            B.sdllm_compact_kv(shape, st["k_full"], st["v_full"], st["idx"], st["k_cache"], st["v_cache"])
+
+    stages = {"dense_block_attn_us": sweep_us(dense_sweep), "score_select_us": sweep_us(score_sweep),
+              "compact_kv_us": sweep_us(compact_sweep), "sparse_attn_us": sparse_launch_us}
+    n_cand = w.seq_len - b
+    stage_bytes = {
+        "dense_block_attn": attn_bytes(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seq_len, b, esize),
+        "score_select": w.batch * w.n_kv_heads * n_cand * w.head_dim * esize + w.batch * w.n_q_heads * b * w.head_dim * esize
+                        + 4 * w.batch * w.n_kv_heads * (2 * n_cand + k_total),
+        "compact_kv": 2 * (2 * w.batch * w.n_kv_heads * k_total * w.head_dim * esize) + 4 * w.batch * w.n_kv_heads * k_total,
+        "sparse_attn": bytes_sparse,
+    }
+    stage_gbs = {k: stage_bytes[k] / (stages[k + "_us"] * 1e-6) / 1e9 for k in stage_bytes}
+
+    result = {
+        "metric": "sparse block-step attention: block-steps/s per layer + achieved HBM GB/s (% of peak)",
+        "value": calls / elapsed,
+        "unit": "block-steps/s per layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {n_layers} layers x (B={w.batch}, Hq={w.n_q_heads}, Hkv={w.n_kv_heads}, "
+                               f"d={w.head_dim}), prompt {w.prompt}, gen {w.gen}, block {b}, {T} steps/block, "
+                               f"r={w.retention}, pool {w.pool_kernel}; one step = one decoding block through all layers",
+                   "block_steps_per_step": T * n_layers, "retained_per_head": k_total},
+        "tokens_per_s_attention_path": w.batch * b * args.steps / elapsed,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "attn_mfma_bf16_kernel (sdllm_sparse_attn, cache_state 2)",
+                     "algorithmic_bytes_per_launch": bytes_sparse, "avg_launch_us": sparse_launch_us},
+        "stages_us_per_layer_call": stages,
+        "stages_algorithmic_gbs": stage_gbs,
+    }
+    if inp0_host is not None:
+        result["cpu_baseline"] = cpu_baseline(w, inp0_host, inp0_host["k_full"].shape[0], None)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

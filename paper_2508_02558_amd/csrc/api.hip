@@ -153,7 +153,9 @@ int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, cons
 
 // ---------------------------------------------------------------- scoring planning
 struct ScorePlan {
+  bool mfma;
   int n_scored;       // candidates that get a score
+  int n_part, tiles_per_part, waves;
   size_t score_bytes, pooled_bytes, ml_bytes;
   size_t ws_bytes() const { return score_bytes + pooled_bytes + ml_bytes; }
 };
@@ -165,7 +167,25 @@ ScorePlan plan_score(const sdllm_shape_t& s) {
   const size_t rows = (size_t)s.batch * s.n_kv_heads;
   pl.score_bytes = align_up(rows * c.n_cand * sizeof(float));
   pl.pooled_bytes = pl.score_bytes;
-  pl.ml_bytes = align_up((size_t)s.batch * s.n_q_heads * 2 * s.block_len * sizeof(float));
+  pl.mfma = s.dtype == SDLLM_BF16 && s.head_dim == 128 && s.block_len == 32 &&
+            score_mfma_supports_group(s.n_q_heads / s.n_kv_heads) && seg_fits_u32(s.kv_stride[2], s.seq_len, 2);
+  pl.n_part = 1;
+  pl.tiles_per_part = 0;
+  pl.waves = 1;
+  if (pl.mfma) {
+    const int n0 = pl.n_scored < c.n_pre ? pl.n_scored : c.n_pre;
+    const int n1 = pl.n_scored - n0;
+    int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
+    if (tiles < 1) tiles = 1;
+    int waves_per_row = (int)((kNumCUs * kMaxWavesPerWg + rows - 1) / rows);
+    if (waves_per_row > tiles) waves_per_row = tiles;
+    if (waves_per_row < 1) waves_per_row = 1;
+    pl.waves = waves_per_row < kMaxWavesPerWg ? waves_per_row : kMaxWavesPerWg;
+    const int n_part = (waves_per_row + pl.waves - 1) / pl.waves;
+    pl.tiles_per_part = (tiles + n_part - 1) / n_part;
+    pl.n_part = (tiles + pl.tiles_per_part - 1) / pl.tiles_per_part;   // no empty part
+  }
+  pl.ml_bytes = align_up((size_t)s.batch * s.n_q_heads * pl.n_part * 2 * s.block_len * sizeof(float));
   return pl;
 }
 
@@ -267,8 +287,8 @@ int32_t sdllm_score_select(const sdllm_shape_t* shape, const void* q_blk, const 
   sp.scale = scale_of(s);
   sp.scale_log2 = sp.scale * kLog2e;
   sp.score = score;
-  sp.n_part = 1; sp.tiles_per_part = 0; sp.part_ml = ml; sp.waves = 1;
-  hipError_t e = launch_score_simple(sp, s.dtype, hs);
+  sp.n_part = pl.n_part; sp.tiles_per_part = pl.tiles_per_part; sp.part_ml = ml; sp.waves = pl.waves;
+  hipError_t e = pl.mfma ? launch_score_mfma_bf16(sp, hs) : launch_score_simple(sp, s.dtype, hs);
   if (e != hipSuccess) return SDLLM_ERR_HIP;
 
   SelectParams q{};

@@ -16,29 +16,13 @@
 //   * up to 8 waves per workgroup split the keys of one head and merge their running
 //     (max, sum, numerator) through LDS; more workgroups per head (split-KV) write fp32
 //     partials that a small combine kernel merges.
-#include "sdllm_internal.h"
+#include "mfma_tile.h"
 
 namespace sdllm {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-// native vectors (not the HIP uint4 struct) so that register arrays of them are promoted to VGPRs
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
-constexpr int kRowBytes = 256 + 16;               // 128 bf16 + one 16-byte pad: rows rotate over the banks
-constexpr int kTileBytes = kTileKeys * kRowBytes; // one 32 x 128 bf16 tile
 constexpr int kWaveLds = 2 * kTileBytes + 512;    // K tile, V tile, (max, sum) exchange
 
 size_t attn_mfma_lds_bytes(int waves) { return (size_t)waves * kWaveLds; }
-
-__device__ __forceinline__ uint32_t tile_off(int row, int chunk) {
-  // padded rows: the sixteen lanes that read one chunk column of sixteen rows hit sixteen different
-  // 16-byte bank groups, and every address is a per-lane base plus a compile-time constant
-  return (uint32_t)(row * kRowBytes + (chunk << 4));
-}
 
 // Tiles never straddle the two key segments: segment 0 contributes ceil(n0/32) tiles, segment 1
 // the rest.  A tile therefore has one wave-uniform base pointer and row count, and K and V (which

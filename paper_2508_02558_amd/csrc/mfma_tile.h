@@ -1,0 +1,51 @@
+// Device helpers shared by the bf16 MFMA kernels: vector types, the padded LDS tile layout and the
+// coalesced 32-key tile load.
+#pragma once
+
+#include "sdllm_internal.h"
+
+namespace sdllm {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+// native vectors (not the HIP uint4 struct) so that register arrays of them are promoted to VGPRs
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kRowBytes = 256 + 16;               // 128 bf16 + one 16-byte pad: rows rotate over the banks
+constexpr int kTileBytes = kTileKeys * kRowBytes; // one 32 x 128 bf16 tile in LDS
+
+__device__ __forceinline__ uint32_t tile_off(int row, int chunk) {
+  // padded rows: the sixteen lanes that read one chunk column of sixteen rows hit sixteen different
+  // 16-byte bank groups, and every address is a per-lane base plus a compile-time constant
+  return (uint32_t)(row * kRowBytes + (chunk << 4));
+}
+
+// Rows [0, rows) of a tile starting at `base` (wave-uniform), `stride` bytes apart: lane l loads the
+// 16-byte chunk l%16 of rows l/16, l/16 + 4, ...  Rows past the end re-read the last valid row.
+__device__ __forceinline__ void load_rows(const char* base, int rows, uint32_t stride, int lane, u32x4 (&reg)[8]) {
+  const uint32_t c16 = (lane & 15) << 4;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    int r = j * 4 + (lane >> 4);
+    r = r < rows ? r : rows - 1;
+    reg[j] = *reinterpret_cast<const u32x4*>(base + (uint32_t)r * stride + c16);
+  }
+}
+
+__device__ __forceinline__ void store_rows(uint8_t* lds_tile, int lane, const u32x4 (&reg)[8]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    *reinterpret_cast<u32x4*>(lds_tile + tile_off(j * 4 + (lane >> 4), lane & 15)) = reg[j];
+}
+
+// make this wave's LDS writes visible to its own later reads (wave-private tiles need no s_barrier)
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+}  // namespace sdllm

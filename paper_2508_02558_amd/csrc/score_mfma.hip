@@ -1,0 +1,290 @@
+// Saliency scoring on the matrix cores for bf16, head_dim 128, 32 query rows (Sec. 3.3 second
+// equation, aggregated over the block's queries and the query heads of a KV group as in Alg. 1).
+//
+// The softmax-normalised score needs each query row's max and sum over ALL candidates before any
+// column can be reduced, so it takes two streaming passes over K (the logits are recomputed; they
+// are cheap next to the K read):
+//   pass 1 (row_stats): logits^T = K_tile Q_h^T, lane = query row, online (max, sum) per row;
+//   pass 2 (col_reduce): logits = Q_h K_tile^T, lane = candidate key, p = exp2(s - max)/sum summed
+//                        over the 32 rows (in registers) and over the G query heads of the group.
+// A workgroup serves one (batch, KV head) and a contiguous range of candidate tiles; its waves take
+// tiles round-robin into wave-private LDS tiles (no barrier in the loop) and the Q fragments of all G
+// heads sit in LDS once per workgroup, so K is read from HBM once per pass however large G is.
+// Probabilities stay fp32 end to end: the retained set must match a float64 reference except for
+// scores within 1e-4 relative of the k-th value.
+#include "mfma_tile.h"
+
+namespace sdllm {
+
+struct CandTiles {
+  const char* k0; const char* k1;   // first row of the prefix / suffix candidates of this (b, g)
+  uint32_t stride;                  // bytes per key row
+  int n0, n1, tiles0;
+};
+
+__device__ __forceinline__ CandTiles cand_tiles(const ScoreParams& p, int b, int g) {
+  CandTiles ct;
+  ct.stride = (uint32_t)(p.k_sr * 2);
+  const char* base = (const char*)p.k + 2 * (b * p.k_sb + g * p.k_sh);
+  ct.k0 = base;
+  ct.k1 = base + (size_t)(p.block_off + p.block_len) * ct.stride;
+  ct.n0 = min(p.n_cand, p.block_off);
+  ct.n1 = p.n_cand - ct.n0;
+  ct.tiles0 = (ct.n0 + kTileKeys - 1) / kTileKeys;
+  return ct;
+}
+
+// tile -> (first row pointer, valid rows, candidate index of its first row)
+__device__ __forceinline__ const char* tile_rows(const CandTiles& ct, int tile, int& rows, int& cand0) {
+  if (tile < ct.tiles0) {
+    cand0 = tile * kTileKeys;
+    rows = min(kTileKeys, ct.n0 - cand0);
+    return ct.k0 + (size_t)cand0 * ct.stride;
+  }
+  const int first = (tile - ct.tiles0) * kTileKeys;
+  cand0 = ct.n0 + first;
+  rows = min(kTileKeys, ct.n1 - first);
+  return ct.k1 + (size_t)first * ct.stride;
+}
+
+// Q rows of all G heads of the group -> LDS, padded like a K tile so both are read the same way.
+template <int G>
+__device__ __forceinline__ void stage_queries(const ScoreParams& p, int b, int g, uint8_t* lds_q) {
+  for (int i = threadIdx.x; i < G * 32 * 16; i += blockDim.x) {
+    const int chunk = i & 15, row = (i >> 4) & 31, hh = i >> 9;
+    const char* src = (const char*)p.q + 2 * (b * p.q_sb + (int64_t)(g * G + hh) * p.q_sh + row * p.q_sr) + chunk * 16;
+    *reinterpret_cast<u32x4*>(lds_q + hh * kTileBytes + tile_off(row, chunk)) = *reinterpret_cast<const u32x4*>(src);
+  }
+}
+
+// ------------------------------------------------------------------ pass 1: row statistics
+template <int G>
+__global__ __launch_bounds__(512) void score_stats_mfma_kernel(const ScoreParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nw = blockDim.x >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int part = blockIdx.x;
+  const int bg = blockIdx.y;
+  const int b = bg / p.hkv, g = bg - b * p.hkv;
+
+  uint8_t* lds_q = smem;
+  uint8_t* lds_k = smem + G * kTileBytes + wave * kTileBytes;
+  stage_queries<G>(p, b, g, lds_q);
+  __syncthreads();
+
+  const CandTiles ct = cand_tiles(p, b, g);
+  const int ntiles = ct.tiles0 + (ct.n1 + kTileKeys - 1) / kTileKeys;
+  const int t_begin = part * p.tiles_per_part;
+  const int t_end = min(ntiles, t_begin + p.tiles_per_part);
+
+  float m_run[G], l_run[G];
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh) { m_run[hh] = -INFINITY; l_run[hh] = 0.f; }
+
+  u32x4 kreg[8];
+  int rows = 0, cand0 = 0;
+  int t = t_begin + wave;
+  if (t < t_end) {
+    const char* src = tile_rows(ct, t, rows, cand0);
+    load_rows(src, rows, ct.stride, lane, kreg);
+  }
+  for (; t < t_end; t += nw) {
+    store_rows(lds_k, lane, kreg);
+    wave_lds_sync();
+    const int rows_now = rows;
+    const int tn = t + nw;
+    if (tn < t_end) {
+      const char* src = tile_rows(ct, tn, rows, cand0);
+      load_rows(src, rows, ct.stride, lane, kreg);
+    }
+    bf16x8 kf[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const bf16x8*>(lds_k + tile_off(col, kk * 2 + half));
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+      f32x16 s;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const bf16x8 qf = *reinterpret_cast<const bf16x8*>(lds_q + hh * kTileBytes + tile_off(col, kk * 2 + half));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf, s, 0, 0, 0);   // rows = keys, columns = queries
+      }
+      float m_loc = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = (i >> 2) * 8 + half * 4 + (i & 3);
+        s[i] = key < rows_now ? s[i] * p.scale_log2 : -INFINITY;
+        m_loc = fmaxf(m_loc, s[i]);
+      }
+      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
+      const float m_new = fmaxf(m_run[hh], m_loc);
+      float l_loc = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) l_loc += __builtin_amdgcn_exp2f(s[i] - m_new);
+      l_run[hh] = l_run[hh] * __builtin_amdgcn_exp2f(m_run[hh] - m_new) + l_loc;
+      m_run[hh] = m_new;
+    }
+    wave_lds_sync();
+  }
+
+  // merge the waves: every wave parks (max, sum) per head and row in its own tile region
+  float* mine = reinterpret_cast<float*>(lds_k);
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh) {
+    const float l_tot = l_run[hh] + __shfl_xor(l_run[hh], 32);
+    if (lane < 32) { mine[hh * 64 + lane] = m_run[hh]; mine[hh * 64 + 32 + lane] = l_tot; }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < G * 32; i += blockDim.x) {
+    const int hh = i >> 5, row = i & 31;
+    float m_tot = -INFINITY;
+    for (int w = 0; w < nw; ++w)
+      m_tot = fmaxf(m_tot, reinterpret_cast<const float*>(smem + (G + w) * kTileBytes)[hh * 64 + row]);
+    float l_tot = 0.f;
+    for (int w = 0; w < nw; ++w) {
+      const float* o = reinterpret_cast<const float*>(smem + (G + w) * kTileBytes);
+      const float m_w = o[hh * 64 + row];
+      if (m_w != -INFINITY) l_tot += o[hh * 64 + 32 + row] * __builtin_amdgcn_exp2f(m_w - m_tot);
+    }
+    const size_t head = (size_t)b * p.hq + g * G + hh;
+    float* dst = p.part_ml + (head * p.n_part + part) * 64;
+    dst[row] = m_tot;
+    dst[32 + row] = l_tot;
+  }
+}
+
+// ------------------------------------------------------------------ pass 2: column reduction
+template <int G>
+__global__ __launch_bounds__(512) void score_cols_mfma_kernel(const ScoreParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nw = blockDim.x >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int part = blockIdx.x;
+  const int bg = blockIdx.y;
+  const int b = bg / p.hkv, g = bg - b * p.hkv;
+
+  uint8_t* lds_q = smem;
+  uint8_t* lds_k = smem + G * kTileBytes + wave * kTileBytes;
+  // per (head, row): max (log2 domain) and 1/sum of the whole row, from the partials of pass 1
+  float2* lds_ml = reinterpret_cast<float2*>(smem + (G + nw) * kTileBytes);
+  stage_queries<G>(p, b, g, lds_q);
+  if (p.softmax) {
+    for (int i = threadIdx.x; i < G * 32; i += blockDim.x) {
+      const int hh = i >> 5, row = i & 31;
+      const size_t head = (size_t)b * p.hq + g * G + hh;
+      const float* src = p.part_ml + head * p.n_part * 64;
+      float m_tot = -INFINITY;
+      for (int s = 0; s < p.n_part; ++s) m_tot = fmaxf(m_tot, src[s * 64 + row]);
+      float l_tot = 0.f;
+      for (int s = 0; s < p.n_part; ++s) {
+        const float m_s = src[s * 64 + row];
+        if (m_s != -INFINITY) l_tot += src[s * 64 + 32 + row] * __builtin_amdgcn_exp2f(m_s - m_tot);
+      }
+      lds_ml[i] = make_float2(m_tot, 1.f / l_tot);
+    }
+  }
+  __syncthreads();
+
+  const CandTiles ct = cand_tiles(p, b, g);
+  const int ntiles = ct.tiles0 + (ct.n1 + kTileKeys - 1) / kTileKeys;
+  const int t_begin = part * p.tiles_per_part;
+  const int t_end = min(ntiles, t_begin + p.tiles_per_part);
+  const float inv_count = 1.f / (float)(G * 32);
+  float* score_row = p.score + (size_t)bg * p.score_stride;
+
+  u32x4 kreg[8];
+  int rows = 0, cand0 = 0;
+  int t = t_begin + wave;
+  if (t < t_end) {
+    const char* src = tile_rows(ct, t, rows, cand0);
+    load_rows(src, rows, ct.stride, lane, kreg);
+  }
+  for (; t < t_end; t += nw) {
+    store_rows(lds_k, lane, kreg);
+    wave_lds_sync();
+    const int rows_now = rows, cand_now = cand0;
+    const int tn = t + nw;
+    if (tn < t_end) {
+      const char* src = tile_rows(ct, tn, rows, cand0);
+      load_rows(src, rows, ct.stride, lane, kreg);
+    }
+    bf16x8 kf[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const bf16x8*>(lds_k + tile_off(col, kk * 2 + half));
+    float total = 0.f;
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+      f32x16 s;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const bf16x8 qf = *reinterpret_cast<const bf16x8*>(lds_q + hh * kTileBytes + tile_off(col, kk * 2 + half));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[kk], s, 0, 0, 0);   // rows = queries, columns = keys
+      }
+      // register i is query row 8*(i/4) + 4*half + i%4, this lane's key is `col`
+      float part_sum = 0.f;
+      if (p.softmax) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float2 ml = lds_ml[hh * 32 + (i >> 2) * 8 + half * 4 + (i & 3)];
+          part_sum += __builtin_amdgcn_exp2f(s[i] * p.scale_log2 - ml.x) * ml.y;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) part_sum += s[i];
+        part_sum *= p.scale;
+      }
+      total += part_sum;
+    }
+    total += __shfl_xor(total, 32);
+    if (half == 0 && col < rows_now) score_row[cand_now + col] = total * inv_count;
+    wave_lds_sync();
+  }
+}
+
+static size_t score_lds_bytes(int group, int waves) { return (size_t)(group + waves) * kTileBytes + (size_t)group * 32 * 8; }
+
+template <int G>
+static hipError_t launch_g(const ScoreParams& p, hipStream_t s) {
+  const size_t lds = score_lds_bytes(G, p.waves);
+  static bool attr_done = false;
+  if (!attr_done) {
+    const int max_lds = (int)score_lds_bytes(G, kMaxWavesPerWg);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_stats_mfma_kernel<G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_cols_mfma_kernel<G>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const dim3 grid(p.n_part, p.batch * p.hkv), block(p.waves * kWave);
+  if (p.softmax) hipLaunchKernelGGL(score_stats_mfma_kernel<G>, grid, block, lds, s, p);
+  hipLaunchKernelGGL(score_cols_mfma_kernel<G>, grid, block, lds, s, p);
+  return hipGetLastError();
+}
+
+bool score_mfma_supports_group(int group) { return group >= 1 && group <= 8; }
+
+hipError_t launch_score_mfma_bf16(const ScoreParams& p, hipStream_t s) {
+  if (p.n_cand <= 0) return hipSuccess;
+  switch (p.group) {
+    case 1: return launch_g<1>(p, s);
+    case 2: return launch_g<2>(p, s);
+    case 3: return launch_g<3>(p, s);
+    case 4: return launch_g<4>(p, s);
+    case 5: return launch_g<5>(p, s);
+    case 6: return launch_g<6>(p, s);
+    case 7: return launch_g<7>(p, s);
+    case 8: return launch_g<8>(p, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace sdllm

@@ -95,6 +95,7 @@ hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s);
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_attn_combine(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_score_mfma_bf16(const ScoreParams& p, hipStream_t s);
+bool score_mfma_supports_group(int group);
 hipError_t launch_score_simple(const ScoreParams& p, int dtype, hipStream_t s);
 hipError_t launch_select(const SelectParams& p, hipStream_t s);
 hipError_t launch_compact(const CompactParams& p, hipStream_t s);
