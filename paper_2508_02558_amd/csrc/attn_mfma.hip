@@ -66,8 +66,8 @@ __device__ __forceinline__ void load_tile(const SegPtrs& sp, int tile, int lane,
     int r = j * 4 + (lane >> 4);
     r = r < ts.rows ? r : ts.rows - 1;           // rows past the end re-read the last key; masked later
     const uint32_t off = (uint32_t)r * stride + c16;
-    kreg[j] = *reinterpret_cast<const u32x4*>(ts.k + off);
-    vreg[j] = *reinterpret_cast<const u32x4*>(ts.v + off);
+    kreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.k + off));   // streamed once
+    vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.v + off));
   }
 }
 

@@ -40,14 +40,14 @@ __global__ __launch_bounds__(256) void compact_kernel(const CompactParams p) {
   u32x4 kv[kRowsPerThread], vv[kRowsPerThread];
 #pragma unroll
   for (int u = 0; u < kRowsPerThread; ++u) {
-    kv[u] = *reinterpret_cast<const u32x4*>(src_k[u]);
-    vv[u] = *reinterpret_cast<const u32x4*>(src_v[u]);
+    kv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src_k[u]));
+    vv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src_v[u]));
   }
 #pragma unroll
   for (int u = 0; u < kRowsPerThread; ++u) {
     if (ok[u]) {
-      *reinterpret_cast<u32x4*>(dst_k[u]) = kv[u];
-      *reinterpret_cast<u32x4*>(dst_v[u]) = vv[u];
+      __builtin_nontemporal_store(kv[u], reinterpret_cast<u32x4*>(dst_k[u]));
+      __builtin_nontemporal_store(vv[u], reinterpret_cast<u32x4*>(dst_v[u]));
     }
   }
 }

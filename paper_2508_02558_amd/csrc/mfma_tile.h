@@ -31,7 +31,8 @@ __device__ __forceinline__ void load_rows(const char* base, int rows, uint32_t s
   for (int j = 0; j < 8; ++j) {
     int r = j * 4 + (lane >> 4);
     r = r < rows ? r : rows - 1;
-    reg[j] = *reinterpret_cast<const u32x4*>(base + (uint32_t)r * stride + c16);
+    // streamed once: non-temporal loads keep the tiles from displacing reusable lines in L2/MALL
+    reg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (uint32_t)r * stride + c16));
   }
 }
 
