@@ -20,7 +20,7 @@
 
 namespace sdllm {
 
-constexpr int kWaveLds = 2 * kTileBytes + 512;    // K tile, V tile, (max, sum) exchange
+constexpr int kWaveLds = 2 * kTileBytes + 512;    // K tile, V tile (later: 64 lanes x 272 B of accumulators), (max, sum)
 
 size_t attn_mfma_lds_bytes(int waves) { return (size_t)waves * kWaveLds; }
 
@@ -71,6 +71,10 @@ __device__ __forceinline__ void load_tile(const SegPtrs& sp, int tile, int lane,
   }
 }
 
+// NSEG = 2: keys are Concat(cache, block) (sparse step); NSEG = 1: one key tensor (dense step, or a
+// sparse step with an empty cache).  The two instantiations also show up as separate kernels in a
+// profile, which keeps sparse and dense launches apart.
+template <int NSEG>
 __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   const int lane = threadIdx.x & 63;
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
 
   SegPtrs sp;
   sp.n0 = p.seg[0].n;
-  sp.n1 = p.seg[1].n;
+  sp.n1 = NSEG == 2 ? p.seg[1].n : 0;
   sp.tiles0 = (sp.n0 + kTileKeys - 1) / kTileKeys;
   sp.r0 = (uint32_t)(p.seg[0].sr * 2);
   sp.r1 = (uint32_t)(p.seg[1].sr * 2);
@@ -209,79 +213,121 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   }
 
   float l_tot = l_run + __shfl_xor(l_run, 32);
+  const size_t slot = (size_t)head * p.n_split + split;
 
-  // merge the waves of this workgroup: waves 1.. park their state in their own LDS region
-  if (nw > 1) {
-    float* my_acc = reinterpret_cast<float*>(smem + wave * kWaveLds);
-    float* my_ml = my_acc + 4096;
-    if (wave > 0) {
+  if (nw == 1) {
+    // a single wave owns the whole result: straight from registers
+    if (p.n_split == 1) {
+      const float inv = 1.f / l_tot;
+      char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+      for (int i = 0; i < 16; ++i) {
+        const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
+        bf16x4 o4;
+        o4[0] = (__bf16)(acc[0][i] * inv);
+        o4[1] = (__bf16)(acc[1][i] * inv);
+        o4[2] = (__bf16)(acc[2][i] * inv);
+        o4[3] = (__bf16)(acc[3][i] * inv);
+        *reinterpret_cast<bf16x4*>(op + mrow * 8) = o4;
+      }
+    } else {
+      float* po = p.part_o + (slot * 32 + col) * 128;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) my_acc[(e * 16 + i) * 64 + lane] = acc[e][i];
-      if (lane < 32) { my_ml[lane] = m_run; my_ml[32 + lane] = l_tot; }
+      for (int i = 0; i < 16; ++i) {
+        const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
+        const f32x4 o4 = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+        *reinterpret_cast<f32x4*>(po + mrow * 4) = o4;
+      }
+      if (lane < 32) {
+        p.part_ml[slot * 64 + lane] = m_run;
+        p.part_ml[slot * 64 + 32 + lane] = l_tot;
+      }
     }
-    __syncthreads();
-    if (wave > 0) return;
-    for (int w = 1; w < nw; ++w) {
-      const float* o_acc = reinterpret_cast<const float*>(smem + w * kWaveLds);
-      const float* o_ml = o_acc + 4096;
-      const float m_o = o_ml[col];
-      const float l_o = o_ml[32 + col];
-      const float m_new = fmaxf(m_run, m_o);
-      // a wave that saw no tile carries (-inf, 0, 0): its factor is 0 whenever m_new is finite
-      const float f_me = m_run == m_new ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
-      const float f_o = m_o == m_new ? 1.f : __builtin_amdgcn_exp2f(m_o - m_new);
-      l_tot = l_tot * f_me + l_o * f_o;
-      m_run = m_new;
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[e][i] = acc[e][i] * f_me + o_acc[(e * 16 + i) * 64 + lane] * f_o;
-    }
+    return;
   }
 
-  if (p.n_split == 1) {
-    const float inv = 1.f / l_tot;
-    char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
+  // Merge the waves of the workgroup, all waves working: every wave parks its 64 accumulator
+  // registers per lane in its own LDS region ([lane][e*16+i], lane stride 272 B) together with its
+  // row (max, sum); after one barrier wave w reduces register slots i = w, w+nw, ... over all waves.
+  {
+    uint8_t* mine = smem + wave * kWaveLds;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
-      bf16x4 o4;
-      o4[0] = (__bf16)(acc[0][i] * inv);
-      o4[1] = (__bf16)(acc[1][i] * inv);
-      o4[2] = (__bf16)(acc[2][i] * inv);
-      o4[3] = (__bf16)(acc[3][i] * inv);
-      *reinterpret_cast<bf16x4*>(op + mrow * 8) = o4;
-    }
-  } else {
-    const size_t slot = (size_t)head * p.n_split + split;
-    float* po = p.part_o + (slot * 32 + col) * 128;
+    for (int e = 0; e < 4; ++e)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
-      f32x4 o4 = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-      *reinterpret_cast<f32x4*>(po + mrow * 4) = o4;
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 v = {acc[e][i4 * 4], acc[e][i4 * 4 + 1], acc[e][i4 * 4 + 2], acc[e][i4 * 4 + 3]};
+        *reinterpret_cast<f32x4*>(mine + lane * kRowBytes + (e * 16 + i4 * 4) * 4) = v;
+      }
+    float* my_ml = reinterpret_cast<float*>(mine + 64 * kRowBytes);
+    if (lane < 32) { my_ml[lane] = m_run; my_ml[32 + lane] = l_tot; }
+  }
+  __syncthreads();
+  float m_tot = -INFINITY;
+  for (int w = 0; w < nw; ++w)
+    m_tot = fmaxf(m_tot, reinterpret_cast<const float*>(smem + w * kWaveLds + 64 * kRowBytes)[col]);
+  float l_all = 0.f;
+  for (int i = wave; i < 16; i += nw) {
+    float o4[4] = {0.f, 0.f, 0.f, 0.f};
+    l_all = 0.f;
+    for (int w = 0; w < nw; ++w) {
+      const uint8_t* src = smem + w * kWaveLds;
+      const float* ml = reinterpret_cast<const float*>(src + 64 * kRowBytes);
+      const float m_w = ml[col];
+      // a wave that saw no tile parked (-inf, 0, 0): factor 0
+      const float f = m_w == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_w - m_tot);
+      l_all += f * ml[32 + col];
+      const float* a = reinterpret_cast<const float*>(src + lane * kRowBytes);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o4[e] += f * a[e * 16 + i];
     }
-    if (lane < 32) {
-      p.part_ml[slot * 64 + lane] = m_run;
-      p.part_ml[slot * 64 + 32 + lane] = l_tot;
+    const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
+    if (p.n_split == 1) {
+      const float inv = 1.f / l_all;
+      bf16x4 ob;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o4[e] * inv);
+      char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
+      *reinterpret_cast<bf16x4*>(op + mrow * 8) = ob;
+    } else {
+      const f32x4 of = {o4[0], o4[1], o4[2], o4[3]};
+      *reinterpret_cast<f32x4*>(p.part_o + (slot * 32 + col) * 128 + mrow * 4) = of;
     }
+  }
+  if (p.n_split > 1 && wave == 0 && lane < 32) {
+    float l0 = 0.f;
+    for (int w = 0; w < nw; ++w) {
+      const float* ml = reinterpret_cast<const float*>(smem + w * kWaveLds + 64 * kRowBytes);
+      const float m_w = ml[lane];
+      l0 += (m_w == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_w - m_tot)) * ml[32 + lane];
+    }
+    p.part_ml[slot * 64 + lane] = m_tot;
+    p.part_ml[slot * 64 + 32 + lane] = l0;
   }
 }
 
-hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s) {
+template <int NSEG>
+static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
   const int nwg = p.batch * p.hq * p.n_split;
-  const size_t lds = attn_mfma_lds_bytes(p.waves);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel<NSEG>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(kMaxWavesPerWg));
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(attn_mfma_bf16_kernel, dim3(nwg), dim3(p.waves * kWave), lds, s, p);
+  hipLaunchKernelGGL(attn_mfma_bf16_kernel<NSEG>, dim3(nwg), dim3(p.waves * kWave), attn_mfma_lds_bytes(p.waves), s, p);
   return hipGetLastError();
+}
+
+hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s) {
+  if (p.seg[0].n > 0 && p.seg[1].n > 0) return launch_nseg<2>(p, s);
+  if (p.seg[1].n > 0) {   // empty cache: the block is the only key tensor
+    AttnParams q = p;
+    q.seg[0] = p.seg[1];
+    q.seg[1].n = 0;
+    return launch_nseg<1>(q, s);
+  }
+  return launch_nseg<1>(p, s);
 }
 
 }  // namespace sdllm
