@@ -28,6 +28,19 @@ def attn_bytes(batch, hq, hkv, d, n_keys, nq, esize):
     return 2 * batch * hkv * n_keys * d * esize + 2 * batch * hq * nq * d * esize
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per sparse-attention launch from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE runs scaled by a plain copy), or None when none is on file."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch[attn_mfma_bf16_kernel<2>]"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, inp0, n_batch, threads_note):
     """The float64 oracle on one layer's block, `n_batch` batch elements, all 32 steps."""
     import numpy as np
@@ -187,6 +200,13 @@ def main() -> int:
         for st in layers:
             B.sdllm_compact_kv(shape, st["k_full"], st["v_full"], st["idx"], st["k_cache"], st["v_cache"])
 
+    # a plain device-to-device copy of known size: the reference dispatch against which HBM byte
+    # counters (FETCH_SIZE / WRITE_SIZE) of a profiler run are scaled
+    calib_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
+
     stages = {"dense_block_attn_us": sweep_us(dense_sweep), "score_select_us": sweep_us(score_sweep),
               "compact_kv_us": sweep_us(compact_sweep), "sparse_attn_us": sparse_launch_us}
     n_cand = w.seq_len - b
@@ -213,7 +233,7 @@ def main() -> int:
                    "block_steps_per_step": T * n_layers, "retained_per_head": k_total},
         "tokens_per_s_attention_path": w.batch * b * args.steps / elapsed,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "kernel": "attn_mfma_bf16_kernel (sdllm_sparse_attn, cache_state 2)",
                      "algorithmic_bytes_per_launch": bytes_sparse, "avg_launch_us": sparse_launch_us},
         "stages_us_per_layer_call": stages,

@@ -1,0 +1,80 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot redo a whole B=8, 32-head layer in seconds, so a few sampled (batch, head) slices
+are recomputed one by one; every other output is covered by properties that hold at any size
+(index sets sorted / in range / right count per segment, compaction equal to a gather)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sdllm_oracle as orc
+from paper_2508_02558_amd import binding as B
+from paper_2508_02558_amd import workloads as wl
+from tests import parity_util as U
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _full_block(w, samples, n_steps=3):
+    print(f"[case] full-size {w.name}: B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} L={w.seq_len} "
+          f"samples={samples}", flush=True)
+    inp = wl.make_block_inputs(w, 0, 0, n_steps, device=DEV)
+    o, b = inp["block_off"], w.block
+    G = w.group
+    shape = U.shape_for(w)
+    k_total, k_pre, k_suf = B.sdllm_retained_count(shape)
+    shape = B.make_shape(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                         seq_len=w.seq_len, block_off=o, block_len=b, dtype=U.DT[w.dtype], retention=w.retention,
+                         pool_kernel=w.pool_kernel, cache_rows=k_total)   # bench.py's cache layout
+    gl = U.GpuLayer(shape, DEV)
+    k_full, v_full = inp["k_full"], inp["v_full"]
+    total_ties = 0
+    for t in range(n_steps):
+        state = orc.cache_state(t, 1)
+        q = inp["q"][t]
+        if state < 2:
+            k_full[:, :, o:o + b] = inp["k_blk"][t]
+            v_full[:, :, o:o + b] = inp["v_blk"][t]
+            assert gl.block_step(t, 1, q, k_full, v_full) == state
+            for (bi, g) in samples:
+                hs = slice(g * G, (g + 1) * G)
+                ref = orc.attention(wl.to_f64(q[bi, hs]), wl.to_f64(k_full[bi, g:g + 1]), wl.to_f64(v_full[bi, g:g + 1]))
+                U.assert_close(gl.out[bi, hs], ref, w.dtype, f"dense step {t} sample {(bi, g)}")
+            if state == 1:
+                idx = gl.idx[:, :, :k_total]
+                # properties that hold for every row, whatever the size
+                idx64 = idx.long()
+                assert bool((idx64[..., 1:] > idx64[..., :-1]).all()), "indices not strictly ascending"
+                assert bool(((idx64 >= 0) & (idx64 < w.seq_len)).all())
+                assert not bool(((idx64 >= o) & (idx64 < o + b)).any()), "a block position was retained"
+                assert bool(((idx64 < o).sum(-1) == k_pre).all()) and bool(((idx64 >= o + b).sum(-1) == k_suf).all())
+                ex = idx64[..., None].expand(-1, -1, -1, w.head_dim)
+                assert torch.equal(gl.k_cache[:, :, :k_total], torch.gather(k_full, 2, ex))
+                assert torch.equal(gl.v_cache[:, :, :k_total], torch.gather(v_full, 2, ex))
+                # sampled rows against the oracle's index set, tie band reported
+                for (bi, g) in samples:
+                    i_orc, pooled_orc, _ = orc.score_select(wl.to_f64(q[bi, g * G:(g + 1) * G]), wl.to_f64(k_full[bi, g:g + 1]),
+                                                            o, b, w.retention, w.pool_kernel)
+                    total_ties += U.compare_index_rows(idx[bi, g].cpu().numpy().astype(np.int64), i_orc[0], pooled_orc[0],
+                                                       w.seq_len, o, b, U.ranked_segments(shape))
+        else:
+            kb, vb = inp["k_blk"][t], inp["v_blk"][t]
+            assert gl.block_step(t, 1, q, kb, vb) == 2
+            for (bi, g) in samples:
+                hs = slice(g * G, (g + 1) * G)
+                kc = torch.cat([gl.k_cache[bi, g:g + 1, :k_total], kb[bi, g:g + 1]], 1)
+                vc = torch.cat([gl.v_cache[bi, g:g + 1, :k_total], vb[bi, g:g + 1]], 1)
+                ref = orc.attention(wl.to_f64(q[bi, hs]), wl.to_f64(kc), wl.to_f64(vc))
+                U.assert_close(gl.out[bi, hs], ref, w.dtype, f"sparse step {t} sample {(bi, g)}")
+    print(f"[done] ties in band over the sampled rows: {total_ties}", flush=True)
+
+
+def test_llada8b_sweep_layer_full_size():
+    # the benchmark workload: B=8, 32 MHA heads, prompt 4096 (one layer of it)
+    _full_block(wl.WORKLOADS["llada8b_sweep"], samples=[(0, 0), (3, 17), (7, 31), (5, 9)])
+
+
+def test_dream_long_full_size():
+    # 28 query / 4 KV heads, prompt 32768, r = 0.25: top-k over 33 248 candidates per row
+    _full_block(wl.WORKLOADS["dream_long"], samples=[(0, 0), (0, 3)])
