@@ -3,7 +3,7 @@
 // logic by nature (Alg. 1 step 9; Alg. 2 / Alg. 5).
 #include <math.h>
 
-#include "../../include/sdllm.h"
+#include "sdllm.h"
 #include "sdllm_internal.h"
 
 using namespace sdllm;

@@ -57,18 +57,10 @@ __device__ __forceinline__ TileSrc tile_src(const SegPtrs& sp, int tile, uint32_
   return ts;
 }
 
-__device__ __forceinline__ void load_tile(const SegPtrs& sp, int tile, int lane, u32x4 (&kreg)[8], u32x4 (&vreg)[8]) {
-  uint32_t stride;
-  const TileSrc ts = tile_src(sp, tile, stride);
-  const uint32_t c16 = (lane & 15) << 4;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    int r = j * 4 + (lane >> 4);
-    r = r < ts.rows ? r : ts.rows - 1;           // rows past the end re-read the last key; masked later
-    const uint32_t off = (uint32_t)r * stride + c16;
-    kreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.k + off));   // streamed once
-    vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.v + off));
-  }
+// One tensor (K or V) of a tile into registers; rows past the end re-read the last valid row and
+// are masked later.  Non-temporal: the cache is streamed once per launch.
+__device__ __forceinline__ void load_half(const char* base, int rows, uint32_t stride, int lane, u32x4 (&reg)[8]) {
+  load_rows(base, rows, stride, lane, reg);
 }
 
 // NSEG = 2: keys are Concat(cache, block) (sparse step); NSEG = 1: one key tensor (dense step, or a
@@ -130,25 +122,24 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   float m_run = -INFINITY;   // running row max (log2 domain), same in both halves
   float l_run = 0.f;         // running row sum over the keys this half-lane has seen
 
-  u32x4 kreg[8], vreg[8];
+  // One staging register set, used alternately for the K and the V tile: a wave keeps exactly one
+  // 8 KB tensor tile in flight (64 KB per CU with 8 waves).  Measured on MI355X, a streaming read
+  // is fastest with 32-64 KB outstanding per CU and loses ~5 % at 128 KB, so K(t+1) flies under the
+  // PV product of tile t and V(t) under its logits/softmax instead of both being prefetched together.
+  u32x4 reg[8];
   int t = t_begin + wave;
-  if (t < t_end) load_tile(sp, t, lane, kreg, vreg);
+  uint32_t stride = 0;
+  TileSrc ts{};
+  if (t < t_end) {
+    ts = tile_src(sp, t, stride);
+    load_half(ts.k, ts.rows, stride, lane, reg);
+  }
 
   for (; t < t_end; t += nw) {
-    // registers -> wave-private LDS tile
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t off = tile_off(j * 4 + (lane >> 4), lane & 15);
-      *reinterpret_cast<u32x4*>(lds_k + off) = kreg[j];
-      *reinterpret_cast<u32x4*>(lds_v + off) = vreg[j];
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // next tile's loads fly while this one is computed
-    const int tn = t + nw;
-    if (tn < t_end) load_tile(sp, tn, lane, kreg, vreg);
+    store_rows(lds_k, lane, reg);
+    wave_lds_sync();
+    load_half(ts.v, ts.rows, stride, lane, reg);   // V(t) flies during the logits and the softmax
+    const int rows = ts.rows;
 
     // logits^T[key, query] = K_tile Q^T
     f32x16 s;
@@ -161,7 +152,6 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     }
     // register i of this lane is key 8*(i/4) + 4*half + i%4 of the tile, query row `col`
     const int key0 = half * 4;
-    const int rows = t < sp.tiles0 ? min(kTileKeys, sp.n0 - t * kTileKeys) : min(kTileKeys, sp.n1 - (t - sp.tiles0) * kTileKeys);
     float m_loc = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -184,6 +174,14 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     for (int e = 0; e < 4; ++e)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[e][i] *= alpha;
+
+    store_rows(lds_v, lane, reg);
+    wave_lds_sync();
+    const int tn = t + nw;
+    if (tn < t_end) {                                // K(t+1) flies during the PV product
+      ts = tile_src(sp, tn, stride);
+      load_half(ts.k, ts.rows, stride, lane, reg);
+    }
 
     // O^T[col 4m+e, query] += V_tile^T P^T, 16 keys per MFMA step
 #pragma unroll
@@ -247,61 +245,63 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   }
 
   // Merge the waves of the workgroup, all waves working: every wave parks its 64 accumulator
-  // registers per lane in its own LDS region ([lane][e*16+i], lane stride 272 B) together with its
+  // registers per lane in its own LDS region ([lane][i][e], lane stride 272 B) together with its
   // row (max, sum); after one barrier wave w reduces register slots i = w, w+nw, ... over all waves.
+  // All LDS reads of a slot are issued before any is used, so the merge costs a few hundred cycles.
   {
     uint8_t* mine = smem + wave * kWaveLds;
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const f32x4 v = {acc[e][i4 * 4], acc[e][i4 * 4 + 1], acc[e][i4 * 4 + 2], acc[e][i4 * 4 + 3]};
-        *reinterpret_cast<f32x4*>(mine + lane * kRowBytes + (e * 16 + i4 * 4) * 4) = v;
-      }
+    for (int i = 0; i < 16; ++i) {
+      const f32x4 v = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+      *reinterpret_cast<f32x4*>(mine + lane * kRowBytes + i * 16) = v;
+    }
     float* my_ml = reinterpret_cast<float*>(mine + 64 * kRowBytes);
     if (lane < 32) { my_ml[lane] = m_run; my_ml[32 + lane] = l_tot; }
   }
   __syncthreads();
-  float m_tot = -INFINITY;
-  for (int w = 0; w < nw; ++w)
-    m_tot = fmaxf(m_tot, reinterpret_cast<const float*>(smem + w * kWaveLds + 64 * kRowBytes)[col]);
-  float l_all = 0.f;
-  for (int i = wave; i < 16; i += nw) {
-    float o4[4] = {0.f, 0.f, 0.f, 0.f};
-    l_all = 0.f;
-    for (int w = 0; w < nw; ++w) {
-      const uint8_t* src = smem + w * kWaveLds;
-      const float* ml = reinterpret_cast<const float*>(src + 64 * kRowBytes);
-      const float m_w = ml[col];
-      // a wave that saw no tile parked (-inf, 0, 0): factor 0
-      const float f = m_w == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_w - m_tot);
-      l_all += f * ml[32 + col];
-      const float* a = reinterpret_cast<const float*>(src + lane * kRowBytes);
+  float f_w[kMaxWavesPerWg];
+  float m_tot = -INFINITY, l_all = 0.f;
+  {
+    float m_w[kMaxWavesPerWg], l_w[kMaxWavesPerWg];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o4[e] += f * a[e * 16 + i];
+    for (int w = 0; w < kMaxWavesPerWg; ++w) {
+      const float* ml = reinterpret_cast<const float*>(smem + w * kWaveLds + 64 * kRowBytes);
+      m_w[w] = w < nw ? ml[col] : -INFINITY;
+      l_w[w] = w < nw ? ml[32 + col] : 0.f;
     }
+#pragma unroll
+    for (int w = 0; w < kMaxWavesPerWg; ++w) m_tot = fmaxf(m_tot, m_w[w]);
+#pragma unroll
+    for (int w = 0; w < kMaxWavesPerWg; ++w) {
+      // a wave that saw no tile parked (-inf, 0, 0): factor 0
+      f_w[w] = m_w[w] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_w[w] - m_tot);
+      l_all += f_w[w] * l_w[w];
+    }
+  }
+  const float inv = 1.f / l_all;
+  for (int i = wave; i < 16; i += nw) {
+    f32x4 part[kMaxWavesPerWg];
+#pragma unroll
+    for (int w = 0; w < kMaxWavesPerWg; ++w)
+      part[w] = w < nw ? *reinterpret_cast<const f32x4*>(smem + w * kWaveLds + lane * kRowBytes + i * 16)
+                       : f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 o4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < kMaxWavesPerWg; ++w) o4 += part[w] * f_w[w];
     const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
     if (p.n_split == 1) {
-      const float inv = 1.f / l_all;
       bf16x4 ob;
 #pragma unroll
       for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o4[e] * inv);
       char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
       *reinterpret_cast<bf16x4*>(op + mrow * 8) = ob;
     } else {
-      const f32x4 of = {o4[0], o4[1], o4[2], o4[3]};
-      *reinterpret_cast<f32x4*>(p.part_o + (slot * 32 + col) * 128 + mrow * 4) = of;
+      *reinterpret_cast<f32x4*>(p.part_o + (slot * 32 + col) * 128 + mrow * 4) = o4;
     }
   }
   if (p.n_split > 1 && wave == 0 && lane < 32) {
-    float l0 = 0.f;
-    for (int w = 0; w < nw; ++w) {
-      const float* ml = reinterpret_cast<const float*>(smem + w * kWaveLds + 64 * kRowBytes);
-      const float m_w = ml[lane];
-      l0 += (m_w == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_w - m_tot)) * ml[32 + lane];
-    }
     p.part_ml[slot * 64 + lane] = m_tot;
-    p.part_ml[slot * 64 + 32 + lane] = l0;
+    p.part_ml[slot * 64 + 32 + lane] = l_all;
   }
 }
 
