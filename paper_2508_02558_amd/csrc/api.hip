@@ -311,6 +311,7 @@ int32_t sdllm_score_select(const sdllm_shape_t* shape, const void* q_blk, const 
     q.n_seg = 1;
     q.seg_begin[0] = 0; q.seg_len[0] = c.n_cand; q.seg_k[0] = c.k_total; q.seg_out[0] = 0;
   }
+  if (!pooled_out && !select_needs_pooled_buffer(q)) q.pooled = nullptr;   // the pooled row then lives in registers only
   e = launch_select(q, hs);
   return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
 }

@@ -63,7 +63,7 @@ struct ScoreParams {
 
 struct SelectParams {
   const float* score;   // [rows, n_cand]
-  float* pooled;        // [rows, n_cand]
+  float* pooled;        // [rows, n_cand]; may be null unless select_needs_pooled_buffer()
   int32_t* idx;         // [rows, k_total]
   int32_t rows;         // B * Hkv
   int32_t n_cand;
@@ -98,6 +98,7 @@ hipError_t launch_score_mfma_bf16(const ScoreParams& p, hipStream_t s);
 bool score_mfma_supports_group(int group);
 hipError_t launch_score_simple(const ScoreParams& p, int dtype, hipStream_t s);
 hipError_t launch_select(const SelectParams& p, hipStream_t s);
+bool select_needs_pooled_buffer(const SelectParams& p);
 hipError_t launch_compact(const CompactParams& p, hipStream_t s);
 
 }  // namespace sdllm
