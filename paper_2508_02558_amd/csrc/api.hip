@@ -124,8 +124,10 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   return pl;
 }
 
+// cand_ml != null (dense MFMA launches only): also emit the scoring pass's row statistics over the
+// candidate keys, n_split partials per query row.
 int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, const KvSegment& b, void* out, void* ws,
-                 size_t ws_bytes, hipStream_t stream) {
+                 size_t ws_bytes, hipStream_t stream, float* cand_ml = nullptr, int cand0_end = 0, int cand1_begin = 0) {
   const AttnPlan pl = plan_attn(s, a.n, a.sr, b.n, b.sr);
   if (pl.ws_bytes() > 0 && (!ws || ws_bytes < pl.ws_bytes())) return SDLLM_ERR_WORKSPACE;
   AttnParams p{};
@@ -141,6 +143,9 @@ int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, cons
   p.n_split = pl.n_split; p.tiles_per_split = pl.tiles_per_split; p.waves = pl.waves;
   p.part_o = (float*)ws;
   p.part_ml = (float*)((char*)ws + pl.part_o_bytes);
+  p.cand_ml = pl.mfma ? cand_ml : nullptr;
+  p.cand0_end = cand0_end;
+  p.cand1_begin = cand1_begin;
   hipError_t e;
   if (pl.mfma) {
     e = launch_attn_mfma_bf16(p, stream);
@@ -194,6 +199,86 @@ int32_t check_q(const sdllm_shape_t& s, const void* q) {
   return SDLLM_OK;
 }
 
+// Alg. 1 steps 2-10.  ext_ml != null: the softmax row statistics over the candidates were already
+// produced (ext_parts partials per row) and only the column reduction and the selection run.
+int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void* k_full, int32_t* idx_out,
+                          float* pooled_out, float* score_out, void* ws, size_t ws_bytes, hipStream_t hs,
+                          float* ext_ml, int ext_parts) {
+  const Counts c = counts_of(s);
+  const ScorePlan pl = plan_score(s);
+  if (!ws || ws_bytes < pl.ws_bytes() || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return SDLLM_ERR_WORKSPACE;
+  if (c.n_cand == 0) return SDLLM_OK;
+
+  float* score = score_out ? score_out : (float*)ws;
+  float* pooled = pooled_out ? pooled_out : (float*)((char*)ws + pl.score_bytes);
+  float* ml = (float*)((char*)ws + pl.score_bytes + pl.pooled_bytes);
+
+  ScoreParams sp{};
+  sp.q = q_blk; sp.k = k_full;
+  sp.q_sb = s.q_stride[0]; sp.q_sh = s.q_stride[1]; sp.q_sr = s.q_stride[2];
+  sp.k_sb = s.kv_stride[0]; sp.k_sh = s.kv_stride[1]; sp.k_sr = s.kv_stride[2];
+  sp.batch = s.batch; sp.hq = s.n_q_heads; sp.hkv = s.n_kv_heads; sp.group = s.n_q_heads / s.n_kv_heads;
+  sp.nq = s.block_len; sp.d = s.head_dim;
+  sp.block_off = s.block_off; sp.block_len = s.block_len;
+  sp.n_cand = pl.n_scored;
+  sp.score_stride = c.n_cand;
+  sp.softmax = s.score_mode == SDLLM_SOFTMAX_MEAN;
+  sp.scale = scale_of(s);
+  sp.scale_log2 = sp.scale * kLog2e;
+  sp.score = score;
+  sp.n_part = pl.n_part; sp.tiles_per_part = pl.tiles_per_part; sp.waves = pl.waves;
+  sp.part_ml = ext_ml ? ext_ml : ml;
+  sp.n_stat_part = ext_ml ? ext_parts : pl.n_part;
+  sp.skip_stats = ext_ml != nullptr;
+  hipError_t e = pl.mfma ? launch_score_mfma_bf16(sp, hs) : launch_score_simple(sp, s.dtype, hs);
+  if (e != hipSuccess) return SDLLM_ERR_HIP;
+
+  SelectParams q{};
+  q.score = score; q.pooled = pooled; q.idx = idx_out;
+  q.rows = s.batch * s.n_kv_heads;
+  q.n_cand = c.n_cand;
+  q.k_total = c.k_total;
+  q.pool_half = (s.pool_kernel - 1) / 2;
+  q.avg_pool = s.pool_mode == SDLLM_AVG_POOL;
+  q.block_off = s.block_off; q.block_len = s.block_len;
+  if (s.evict_scope == SDLLM_EVICT_PREFIX_ONLY) {
+    q.n_seg = 1;
+    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
+    q.tail_begin = c.n_pre; q.tail_len = c.n_suf; q.tail_out = c.k_pre;
+  } else if (s.select_mode == SDLLM_PER_SEGMENT) {
+    q.n_seg = 2;
+    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
+    q.seg_begin[1] = c.n_pre; q.seg_len[1] = c.n_suf; q.seg_k[1] = c.k_suf; q.seg_out[1] = c.k_pre;
+  } else {
+    q.n_seg = 1;
+    q.seg_begin[0] = 0; q.seg_len[0] = c.n_cand; q.seg_k[0] = c.k_total; q.seg_out[0] = 0;
+  }
+  if (!pooled_out && !select_needs_pooled_buffer(q)) q.pooled = nullptr;   // the pooled row then lives in registers only
+  e = launch_select(q, hs);
+  return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
+}
+
+// Workspace of sdllm_block_step: [0, base) is shared by the attention partials and the scoring
+// buffers (used one after the other on the stream); the fused row statistics of the cache-update
+// step live behind it because they are written by the attention and read by the scoring.
+struct BlockStepWs { size_t base, stats_bytes; int stats_parts; bool fuse; };
+
+BlockStepWs plan_block_step(const sdllm_shape_t& s) {
+  const Counts c = counts_of(s);
+  const AttnPlan dense = plan_attn(s, s.seq_len, s.kv_stride[2], 0, 0);
+  const AttnPlan sparse = plan_attn(s, c.k_total, s.cache_stride[2], s.block_len, s.blk_stride[2]);
+  const ScorePlan sc = plan_score(s);
+  BlockStepWs w{};
+  w.base = dense.ws_bytes();
+  if (sparse.ws_bytes() > w.base) w.base = sparse.ws_bytes();
+  if (sc.ws_bytes() > w.base) w.base = sc.ws_bytes();
+  w.base = align_up(w.base);
+  w.fuse = dense.mfma && sc.mfma && s.score_mode == SDLLM_SOFTMAX_MEAN && c.n_cand > 0;
+  w.stats_parts = dense.n_split;
+  w.stats_bytes = w.fuse ? align_up((size_t)s.batch * s.n_q_heads * dense.n_split * 64 * sizeof(float)) : 0;
+  return w;
+}
+
 }  // namespace
 
 // ================================================================ exported functions
@@ -242,12 +327,8 @@ int32_t sdllm_workspace_bytes(const sdllm_shape_t* shape, int32_t op, int32_t n_
       need = plan_attn(s, n_cached, s.cache_stride[2], s.block_len, s.blk_stride[2]).ws_bytes();
       break;
     case SDLLM_OP_BLOCK_STEP: {
-      const Counts c = counts_of(s);
-      const size_t a = plan_attn(s, s.seq_len, s.kv_stride[2], 0, 0).ws_bytes();
-      const size_t b = plan_attn(s, c.k_total, s.cache_stride[2], s.block_len, s.blk_stride[2]).ws_bytes();
-      const size_t d = plan_score(s).ws_bytes();
-      need = a > b ? a : b;
-      need = need > d ? need : d;
+      const BlockStepWs w = plan_block_step(s);
+      need = w.base + w.stats_bytes;
       break;
     }
     default: return SDLLM_ERR_INVALID_ARG;
@@ -263,57 +344,8 @@ int32_t sdllm_score_select(const sdllm_shape_t* shape, const void* q_blk, const 
   const sdllm_shape_t& s = *shape;
   if ((st = check_q(s, q_blk)) != SDLLM_OK) return st;
   if (!k_full || !aligned16(k_full) || !row_stride_ok(s.kv_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
-  const Counts c = counts_of(s);
-  if (c.k_total > 0 && !idx_out) return SDLLM_ERR_INVALID_ARG;
-  const ScorePlan pl = plan_score(s);
-  if (!ws || ws_bytes < pl.ws_bytes() || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return SDLLM_ERR_WORKSPACE;
-  if (c.n_cand == 0) return SDLLM_OK;
-  hipStream_t hs = (hipStream_t)stream;
-
-  float* score = score_out ? score_out : (float*)ws;
-  float* pooled = pooled_out ? pooled_out : (float*)((char*)ws + pl.score_bytes);
-  float* ml = (float*)((char*)ws + pl.score_bytes + pl.pooled_bytes);
-
-  ScoreParams sp{};
-  sp.q = q_blk; sp.k = k_full;
-  sp.q_sb = s.q_stride[0]; sp.q_sh = s.q_stride[1]; sp.q_sr = s.q_stride[2];
-  sp.k_sb = s.kv_stride[0]; sp.k_sh = s.kv_stride[1]; sp.k_sr = s.kv_stride[2];
-  sp.batch = s.batch; sp.hq = s.n_q_heads; sp.hkv = s.n_kv_heads; sp.group = s.n_q_heads / s.n_kv_heads;
-  sp.nq = s.block_len; sp.d = s.head_dim;
-  sp.block_off = s.block_off; sp.block_len = s.block_len;
-  sp.n_cand = pl.n_scored;
-  sp.score_stride = c.n_cand;
-  sp.softmax = s.score_mode == SDLLM_SOFTMAX_MEAN;
-  sp.scale = scale_of(s);
-  sp.scale_log2 = sp.scale * kLog2e;
-  sp.score = score;
-  sp.n_part = pl.n_part; sp.tiles_per_part = pl.tiles_per_part; sp.part_ml = ml; sp.waves = pl.waves;
-  hipError_t e = pl.mfma ? launch_score_mfma_bf16(sp, hs) : launch_score_simple(sp, s.dtype, hs);
-  if (e != hipSuccess) return SDLLM_ERR_HIP;
-
-  SelectParams q{};
-  q.score = score; q.pooled = pooled; q.idx = idx_out;
-  q.rows = s.batch * s.n_kv_heads;
-  q.n_cand = c.n_cand;
-  q.k_total = c.k_total;
-  q.pool_half = (s.pool_kernel - 1) / 2;
-  q.avg_pool = s.pool_mode == SDLLM_AVG_POOL;
-  q.block_off = s.block_off; q.block_len = s.block_len;
-  if (s.evict_scope == SDLLM_EVICT_PREFIX_ONLY) {
-    q.n_seg = 1;
-    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
-    q.tail_begin = c.n_pre; q.tail_len = c.n_suf; q.tail_out = c.k_pre;
-  } else if (s.select_mode == SDLLM_PER_SEGMENT) {
-    q.n_seg = 2;
-    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
-    q.seg_begin[1] = c.n_pre; q.seg_len[1] = c.n_suf; q.seg_k[1] = c.k_suf; q.seg_out[1] = c.k_pre;
-  } else {
-    q.n_seg = 1;
-    q.seg_begin[0] = 0; q.seg_len[0] = c.n_cand; q.seg_k[0] = c.k_total; q.seg_out[0] = 0;
-  }
-  if (!pooled_out && !select_needs_pooled_buffer(q)) q.pooled = nullptr;   // the pooled row then lives in registers only
-  e = launch_select(q, hs);
-  return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
+  if (counts_of(s).k_total > 0 && !idx_out) return SDLLM_ERR_INVALID_ARG;
+  return score_select_impl(s, q_blk, k_full, idx_out, pooled_out, score_out, ws, ws_bytes, (hipStream_t)stream, nullptr, 0);
 }
 
 int32_t sdllm_compact_kv(const sdllm_shape_t* shape, const void* k_full, const void* v_full, const int32_t* idx,
@@ -383,9 +415,18 @@ int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int3
   if (state == SDLLM_STATE_UPDATE && c.k_total > 0 && (!idx || !k_cache || !v_cache)) return SDLLM_ERR_INVALID_ARG;
   KvSegment a{k_in, v_in, s.kv_stride[0], s.kv_stride[1], s.kv_stride[2], s.seq_len};
   KvSegment b{nullptr, nullptr, 0, 0, 0, 0};
-  st = run_attn(s, q_blk, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+  const BlockStepWs w = plan_block_step(s);
+  if (state == SDLLM_STATE_FULL || !w.fuse)
+    st = run_attn(s, q_blk, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+  else {
+    // cache-update step: the dense attention also leaves the scoring softmax's row statistics
+    const int cand1 = s.evict_scope == SDLLM_EVICT_PREFIX_ONLY ? s.seq_len : s.block_off + s.block_len;
+    st = run_attn(s, q_blk, a, b, out, ws, w.base, (hipStream_t)stream, (float*)((char*)ws + w.base), s.block_off, cand1);
+  }
   if (st != SDLLM_OK || state == SDLLM_STATE_FULL) return st;
-  st = sdllm_score_select(shape, q_blk, k_in, idx, nullptr, nullptr, ws, ws_bytes, stream);
+  if (!row_stride_ok(s.q_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
+  st = score_select_impl(s, q_blk, k_in, idx, nullptr, nullptr, ws, w.base, (hipStream_t)stream,
+                         w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts);
   if (st != SDLLM_OK) return st;
   return sdllm_compact_kv(shape, k_in, v_in, idx, k_cache, v_cache, stream);
 }

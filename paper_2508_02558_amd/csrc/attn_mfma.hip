@@ -66,7 +66,9 @@ __device__ __forceinline__ void load_half(const char* base, int rows, uint32_t s
 // NSEG = 2: keys are Concat(cache, block) (sparse step); NSEG = 1: one key tensor (dense step, or a
 // sparse step with an empty cache).  The two instantiations also show up as separate kernels in a
 // profile, which keeps sparse and dense launches apart.
-template <int NSEG>
+// STATS (dense launches of the cache-update step only): also accumulate each query row's (max, sum)
+// over the candidate keys, so the scoring pass that follows need not stream K for them again.
+template <int NSEG, bool STATS>
 __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   const int lane = threadIdx.x & 63;
@@ -121,6 +123,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     for (int i = 0; i < 16; ++i) acc[e][i] = 0.f;
   float m_run = -INFINITY;   // running row max (log2 domain), same in both halves
   float l_run = 0.f;         // running row sum over the keys this half-lane has seen
+  float mc_run = -INFINITY, lc_run = 0.f;   // the same over candidate keys only (STATS)
 
   // One staging register set, used alternately for the K and the V tile: a wave keeps exactly one
   // 8 KB tensor tile in flight (64 KB per CU with 8 waves).  Measured on MI355X, a streaming read
@@ -158,6 +161,28 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
       const int key = key0 + (i >> 2) * 8 + (i & 3);
       s[i] = key < rows ? s[i] * p.scale_log2 : -INFINITY;
       m_loc = fmaxf(m_loc, s[i]);
+    }
+    if (STATS) {
+      // single segment: register i is absolute position 32 t + key; the block's own keys (and, for
+      // prefix-only eviction, the suffix) are not candidates
+      const int pos0 = t * kTileKeys + key0;
+      float sc[16];
+      float mc_loc = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int pos = pos0 + (i >> 2) * 8 + (i & 3);
+        sc[i] = (pos < p.cand0_end || pos >= p.cand1_begin) ? s[i] : -INFINITY;
+        mc_loc = fmaxf(mc_loc, sc[i]);
+      }
+      mc_loc = fmaxf(mc_loc, __shfl_xor(mc_loc, 32));
+      const float mc_new = fmaxf(mc_run, mc_loc);
+      if (mc_new != -INFINITY) {
+        float lc_loc = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) lc_loc += __builtin_amdgcn_exp2f(sc[i] - mc_new);
+        lc_run = lc_run * __builtin_amdgcn_exp2f(mc_run - mc_new) + lc_loc;
+        mc_run = mc_new;
+      }
     }
     m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
     const float m_new = fmaxf(m_run, m_loc);
@@ -211,10 +236,15 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   }
 
   float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float lc_tot = lc_run + __shfl_xor(lc_run, 32);
   const size_t slot = (size_t)head * p.n_split + split;
 
   if (nw == 1) {
     // a single wave owns the whole result: straight from registers
+    if (STATS && lane < 32) {
+      p.cand_ml[slot * 64 + lane] = mc_run;
+      p.cand_ml[slot * 64 + 32 + lane] = lc_tot;
+    }
     if (p.n_split == 1) {
       const float inv = 1.f / l_tot;
       char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
@@ -256,9 +286,23 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
       *reinterpret_cast<f32x4*>(mine + lane * kRowBytes + i * 16) = v;
     }
     float* my_ml = reinterpret_cast<float*>(mine + 64 * kRowBytes);
-    if (lane < 32) { my_ml[lane] = m_run; my_ml[32 + lane] = l_tot; }
+    if (lane < 32) {
+      my_ml[lane] = m_run; my_ml[32 + lane] = l_tot;
+      if (STATS) { my_ml[64 + lane] = mc_run; my_ml[96 + lane] = lc_tot; }
+    }
   }
   __syncthreads();
+  if (STATS && wave == 0 && lane < 32) {
+    float mc = -INFINITY, lc = 0.f;
+    for (int w = 0; w < nw; ++w)
+      mc = fmaxf(mc, reinterpret_cast<const float*>(smem + w * kWaveLds + 64 * kRowBytes)[64 + lane]);
+    for (int w = 0; w < nw; ++w) {
+      const float* ml = reinterpret_cast<const float*>(smem + w * kWaveLds + 64 * kRowBytes);
+      if (ml[64 + lane] != -INFINITY) lc += ml[96 + lane] * __builtin_amdgcn_exp2f(ml[64 + lane] - mc);
+    }
+    p.cand_ml[slot * 64 + lane] = mc;
+    p.cand_ml[slot * 64 + 32 + lane] = lc;
+  }
   float f_w[kMaxWavesPerWg];
   float m_tot = -INFINITY, l_all = 0.f;
   {
@@ -305,29 +349,29 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   }
 }
 
-template <int NSEG>
+template <int NSEG, bool STATS>
 static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
   const int nwg = p.batch * p.hq * p.n_split;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel<NSEG>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel<NSEG, STATS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(kMaxWavesPerWg));
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(attn_mfma_bf16_kernel<NSEG>, dim3(nwg), dim3(p.waves * kWave), attn_mfma_lds_bytes(p.waves), s, p);
+  hipLaunchKernelGGL((attn_mfma_bf16_kernel<NSEG, STATS>), dim3(nwg), dim3(p.waves * kWave), attn_mfma_lds_bytes(p.waves), s, p);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s) {
-  if (p.seg[0].n > 0 && p.seg[1].n > 0) return launch_nseg<2>(p, s);
+  if (p.seg[0].n > 0 && p.seg[1].n > 0) return launch_nseg<2, false>(p, s);
   if (p.seg[1].n > 0) {   // empty cache: the block is the only key tensor
     AttnParams q = p;
     q.seg[0] = p.seg[1];
     q.seg[1].n = 0;
-    return launch_nseg<1>(q, s);
+    return launch_nseg<1, false>(q, s);
   }
-  return launch_nseg<1>(p, s);
+  return p.cand_ml ? launch_nseg<1, true>(p, s) : launch_nseg<1, false>(p, s);
 }
 
 }  // namespace sdllm

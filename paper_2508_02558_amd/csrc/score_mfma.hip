@@ -177,11 +177,11 @@ __global__ __launch_bounds__(512) void score_cols_mfma_kernel(const ScoreParams 
     for (int i = threadIdx.x; i < G * 32; i += blockDim.x) {
       const int hh = i >> 5, row = i & 31;
       const size_t head = (size_t)b * p.hq + g * G + hh;
-      const float* src = p.part_ml + head * p.n_part * 64;
+      const float* src = p.part_ml + head * p.n_stat_part * 64;
       float m_tot = -INFINITY;
-      for (int s = 0; s < p.n_part; ++s) m_tot = fmaxf(m_tot, src[s * 64 + row]);
+      for (int s = 0; s < p.n_stat_part; ++s) m_tot = fmaxf(m_tot, src[s * 64 + row]);
       float l_tot = 0.f;
-      for (int s = 0; s < p.n_part; ++s) {
+      for (int s = 0; s < p.n_stat_part; ++s) {
         const float m_s = src[s * 64 + row];
         if (m_s != -INFINITY) l_tot += src[s * 64 + 32 + row] * __builtin_amdgcn_exp2f(m_s - m_tot);
       }
@@ -265,7 +265,7 @@ static hipError_t launch_g(const ScoreParams& p, hipStream_t s) {
     attr_done = true;
   }
   const dim3 grid(p.n_part, p.batch * p.hkv), block(p.waves * kWave);
-  if (p.softmax) hipLaunchKernelGGL(score_stats_mfma_kernel<G>, grid, block, lds, s, p);
+  if (p.softmax && !p.skip_stats) hipLaunchKernelGGL(score_stats_mfma_kernel<G>, grid, block, lds, s, p);
   hipLaunchKernelGGL(score_cols_mfma_kernel<G>, grid, block, lds, s, p);
   return hipGetLastError();
 }

@@ -38,6 +38,12 @@ struct AttnParams {
   int32_t waves;            // waves per workgroup
   float* part_o;            // [B*Hq, n_split, nq, d] fp32 partial numerators (n_split > 1)
   float* part_ml;           // [B*Hq, n_split, 2, nq] running max (log2 domain) and denominator
+  // Optional by-product of a dense (single-segment) launch: the softmax row statistics of the
+  // scoring pass, i.e. (max, sum) per query row over the CANDIDATE keys only, which are the keys
+  // outside [cand0_end, cand1_begin).  Layout [B*Hq, n_split, 2, nq], the layout the scoring
+  // kernels read their partial statistics in.  Null: not produced.
+  float* cand_ml;
+  int32_t cand0_end, cand1_begin;
 };
 
 // Scoring of the candidates K_f = Concat[K_{:o}, K_{o+b:}] against the block's queries.
@@ -55,9 +61,11 @@ struct ScoreParams {
   float* score;         // [B*Hkv, score_stride], the first n_cand of each row written
   int32_t score_stride;
   // row statistics of the softmax (pass 1 -> pass 2)
-  int32_t n_part;       // partial (max, sum) pairs per query row
+  int32_t n_part;       // workgroups per (batch, KV head) row of the scoring kernels
   int32_t tiles_per_part;
-  float* part_ml;       // [B*Hq, n_part, 2, nq]
+  float* part_ml;       // [B*Hq, n_stat_part, 2, nq]
+  int32_t n_stat_part;  // partial (max, sum) pairs per query row in part_ml
+  int32_t skip_stats;   // 1: part_ml was already filled (by the dense attention of the same step)
   int32_t waves;
 };
 
