@@ -88,6 +88,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 // ---------------------------------------------------------------- attention planning
 struct AttnPlan {
   bool mfma;
+  bool gqa;   // grouped-query kernel: one workgroup per (batch, KV head), wave = query head
   int n_split, tiles_per_split, waves;
   size_t part_o_bytes, part_ml_bytes;
   size_t ws_bytes() const { return part_o_bytes + part_ml_bytes; }
@@ -104,7 +105,26 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   pl.n_split = 1;
   pl.tiles_per_split = 0;
   pl.waves = 1;
-  if (pl.mfma) {
+  // The shared-tile grouped-query kernel pays a workgroup barrier per tile; it wins once every CU has
+  // at least two query heads to serve (measured: B*Hq >= 512), below that one workgroup per head
+  // finishes sooner even though K/V are then read G times from L2.
+  pl.gqa = pl.mfma && attn_gqa_supports_group(s.n_q_heads / s.n_kv_heads) && s.batch * s.n_q_heads >= 2 * kNumCUs;
+  if (pl.gqa) {
+    const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
+    const int rows = s.batch * s.n_kv_heads;
+    // one workgroup per CU if the keys allow it, but never fewer than 4 tiles (two LDS stages) each
+    int n_split = (kNumCUs + rows - 1) / rows;
+    const int max_split = tiles / 4 > 1 ? tiles / 4 : 1;
+    if (n_split > max_split) n_split = max_split;
+    pl.tiles_per_split = (tiles + n_split - 1) / n_split;
+    pl.n_split = (tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;
+    pl.waves = s.n_q_heads / s.n_kv_heads;
+    if (pl.n_split > 1) {
+      const size_t slots = (size_t)s.batch * s.n_q_heads * pl.n_split;
+      pl.part_o_bytes = align_up(slots * s.block_len * s.head_dim * sizeof(float));
+      pl.part_ml_bytes = align_up(slots * 2 * s.block_len * sizeof(float));
+    }
+  } else if (pl.mfma) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int heads = s.batch * s.n_q_heads;
     // aim at 8 waves on every CU, never more waves than tiles
@@ -143,12 +163,12 @@ int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, cons
   p.n_split = pl.n_split; p.tiles_per_split = pl.tiles_per_split; p.waves = pl.waves;
   p.part_o = (float*)ws;
   p.part_ml = (float*)((char*)ws + pl.part_o_bytes);
-  p.cand_ml = pl.mfma ? cand_ml : nullptr;
+  p.cand_ml = pl.mfma && !pl.gqa ? cand_ml : nullptr;
   p.cand0_end = cand0_end;
   p.cand1_begin = cand1_begin;
   hipError_t e;
   if (pl.mfma) {
-    e = launch_attn_mfma_bf16(p, stream);
+    e = pl.gqa ? launch_attn_gqa_mfma_bf16(p, stream) : launch_attn_mfma_bf16(p, stream);
     if (e == hipSuccess && pl.n_split > 1) e = launch_attn_combine(p, s.dtype, stream);
   } else {
     e = launch_attn_simple(p, s.dtype, stream);
@@ -273,7 +293,7 @@ BlockStepWs plan_block_step(const sdllm_shape_t& s) {
   if (sparse.ws_bytes() > w.base) w.base = sparse.ws_bytes();
   if (sc.ws_bytes() > w.base) w.base = sc.ws_bytes();
   w.base = align_up(w.base);
-  w.fuse = dense.mfma && sc.mfma && s.score_mode == SDLLM_SOFTMAX_MEAN && c.n_cand > 0;
+  w.fuse = dense.mfma && !dense.gqa && sc.mfma && s.score_mode == SDLLM_SOFTMAX_MEAN && c.n_cand > 0;
   w.stats_parts = dense.n_split;
   w.stats_bytes = w.fuse ? align_up((size_t)s.batch * s.n_q_heads * dense.n_split * 64 * sizeof(float)) : 0;
   return w;

@@ -16,52 +16,13 @@
 //   * up to 8 waves per workgroup split the keys of one head and merge their running
 //     (max, sum, numerator) through LDS; more workgroups per head (split-KV) write fp32
 //     partials that a small combine kernel merges.
-#include "mfma_tile.h"
+#include "attn_tile_math.h"
 
 namespace sdllm {
 
 constexpr int kWaveLds = 2 * kTileBytes + 512;    // K tile, V tile (later: 64 lanes x 272 B of accumulators), (max, sum)
 
 size_t attn_mfma_lds_bytes(int waves) { return (size_t)waves * kWaveLds; }
-
-// Tiles never straddle the two key segments: segment 0 contributes ceil(n0/32) tiles, segment 1
-// the rest.  A tile therefore has one wave-uniform base pointer and row count, and K and V (which
-// share strides) are addressed with the same eight per-lane 32-bit byte offsets.
-struct TileSrc {
-  const char* k;
-  const char* v;
-  int rows;        // valid keys in this tile (1..32)
-};
-
-struct SegPtrs {
-  const char* k0; const char* v0; uint32_t r0;   // byte stride per row, segment 0
-  const char* k1; const char* v1; uint32_t r1;
-  int n0, n1, tiles0;
-};
-
-__device__ __forceinline__ TileSrc tile_src(const SegPtrs& sp, int tile, uint32_t& row_stride) {
-  TileSrc ts;
-  if (tile < sp.tiles0) {
-    const int first = tile * kTileKeys;
-    ts.k = sp.k0 + (size_t)first * sp.r0;
-    ts.v = sp.v0 + (size_t)first * sp.r0;
-    ts.rows = min(kTileKeys, sp.n0 - first);
-    row_stride = sp.r0;
-  } else {
-    const int first = (tile - sp.tiles0) * kTileKeys;
-    ts.k = sp.k1 + (size_t)first * sp.r1;
-    ts.v = sp.v1 + (size_t)first * sp.r1;
-    ts.rows = min(kTileKeys, sp.n1 - first);
-    row_stride = sp.r1;
-  }
-  return ts;
-}
-
-// One tensor (K or V) of a tile into registers; rows past the end re-read the last valid row and
-// are masked later.  Non-temporal: the cache is streamed once per launch.
-__device__ __forceinline__ void load_half(const char* base, int rows, uint32_t stride, int lane, u32x4 (&reg)[8]) {
-  load_rows(base, rows, stride, lane, reg);
-}
 
 // NSEG = 2: keys are Concat(cache, block) (sparse step); NSEG = 1: one key tensor (dense step, or a
 // sparse step with an empty cache).  The two instantiations also show up as separate kernels in a
@@ -88,30 +49,14 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   const int h = head - b * p.hq;
   const int g = h / p.group;
 
-  SegPtrs sp;
-  sp.n0 = p.seg[0].n;
-  sp.n1 = NSEG == 2 ? p.seg[1].n : 0;
-  sp.tiles0 = (sp.n0 + kTileKeys - 1) / kTileKeys;
-  sp.r0 = (uint32_t)(p.seg[0].sr * 2);
-  sp.r1 = (uint32_t)(p.seg[1].sr * 2);
-  sp.k0 = (const char*)p.seg[0].k + 2 * (b * p.seg[0].sb + g * p.seg[0].sh);
-  sp.v0 = (const char*)p.seg[0].v + 2 * (b * p.seg[0].sb + g * p.seg[0].sh);
-  sp.k1 = (const char*)p.seg[1].k + 2 * (b * p.seg[1].sb + g * p.seg[1].sh);
-  sp.v1 = (const char*)p.seg[1].v + 2 * (b * p.seg[1].sb + g * p.seg[1].sh);
+  const SegPtrs sp = seg_ptrs(p, b, g, NSEG == 2);
   const int ntiles = sp.tiles0 + (sp.n1 + kTileKeys - 1) / kTileKeys;
   const int t_begin = split * p.tiles_per_split;
   const int t_end = min(ntiles, t_begin + p.tiles_per_split);
 
   // Q^T fragments (B operand): lane (col = query row, half) holds head-dim [16t + 8 half, +8)
   bf16x8 qf[8];
-  {
-    const u32x4* qp = reinterpret_cast<const u32x4*>((const char*)p.q + 2 * (b * p.q_sb + h * p.q_sh + col * p.q_sr));
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      u32x4 raw = qp[t * 2 + half];
-      qf[t] = __builtin_bit_cast(bf16x8, raw);
-    }
-  }
+  load_q_frags((const char*)p.q + 2 * (b * p.q_sb + h * p.q_sh + col * p.q_sr), half, qf);
 
   uint8_t* lds_k = smem + wave * kWaveLds;
   uint8_t* lds_v = lds_k + kTileBytes;
@@ -121,7 +66,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   for (int e = 0; e < 4; ++e)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[e][i] = 0.f;
-  float m_run = -INFINITY;   // running row max (log2 domain), same in both halves
+  float m_run = -INFINITY;   // softmax reference of the row (log2 domain, within 8 of the running max), same in both halves
   float l_run = 0.f;         // running row sum over the keys this half-lane has seen
   float mc_run = -INFINITY, lc_run = 0.f;   // the same over candidate keys only (STATS)
 
@@ -135,33 +80,19 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   TileSrc ts{};
   if (t < t_end) {
     ts = tile_src(sp, t, stride);
-    load_half(ts.k, ts.rows, stride, lane, reg);
+    load_rows(ts.k, ts.rows, stride, lane, reg);
   }
 
   for (; t < t_end; t += nw) {
     store_rows(lds_k, lane, reg);
     wave_lds_sync();
-    load_half(ts.v, ts.rows, stride, lane, reg);   // V(t) flies during the logits and the softmax
+    load_rows(ts.v, ts.rows, stride, lane, reg);   // V(t) flies during the logits and the softmax
     const int rows = ts.rows;
 
-    // logits^T[key, query] = K_tile Q^T
+    // logits^T[key, query] = K_tile Q^T (raw), row max in the scaled log2 domain
     f32x16 s;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s[i] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(lds_k + tile_off(col, kk * 2 + half));
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s, 0, 0, 0);
-    }
-    // register i of this lane is key 8*(i/4) + 4*half + i%4 of the tile, query row `col`
+    const float m_loc = tile_logits(lds_k, qf, rows, p.scale_log2, half, col, s);
     const int key0 = half * 4;
-    float m_loc = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int key = key0 + (i >> 2) * 8 + (i & 3);
-      s[i] = key < rows ? s[i] * p.scale_log2 : -INFINITY;
-      m_loc = fmaxf(m_loc, s[i]);
-    }
     if (STATS) {
       // single segment: register i is absolute position 32 t + key; the block's own keys (and, for
       // prefix-only eviction, the suffix) are not candidates
@@ -171,7 +102,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int pos = pos0 + (i >> 2) * 8 + (i & 3);
-        sc[i] = (pos < p.cand0_end || pos >= p.cand1_begin) ? s[i] : -INFINITY;
+        sc[i] = (pos < p.cand0_end || pos >= p.cand1_begin) ? s[i] * p.scale_log2 : -INFINITY;
         mc_loc = fmaxf(mc_loc, sc[i]);
       }
       mc_loc = fmaxf(mc_loc, __shfl_xor(mc_loc, 32));
@@ -184,53 +115,17 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
         mc_run = mc_new;
       }
     }
-    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
-    const float m_new = fmaxf(m_run, m_loc);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    float l_loc = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      s[i] = __builtin_amdgcn_exp2f(s[i] - m_new);
-      l_loc += s[i];
-    }
-    l_run = l_run * alpha + l_loc;
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[e][i] *= alpha;
+    tile_softmax(s, m_loc, p.scale_log2, m_run, l_run, acc);
 
     store_rows(lds_v, lane, reg);
     wave_lds_sync();
     const int tn = t + nw;
     if (tn < t_end) {                                // K(t+1) flies during the PV product
       ts = tile_src(sp, tn, stride);
-      load_half(ts.k, ts.rows, stride, lane, reg);
+      load_rows(ts.k, ts.rows, stride, lane, reg);
     }
 
-    // O^T[col 4m+e, query] += V_tile^T P^T, 16 keys per MFMA step
-#pragma unroll
-    for (int step = 0; step < 2; ++step) {
-      bf16x8 pb;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) pb[j] = (__bf16)s[step * 8 + j];
-      u32x2 vv[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int key_local = step * 16 + (j >> 2) * 8 + half * 4 + (j & 3);
-        vv[j] = *reinterpret_cast<const u32x2*>(lds_v + tile_off(key_local, col >> 1) + ((col & 1) << 3));
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        u32x4 w;
-        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        w.x = __builtin_amdgcn_perm(e < 2 ? vv[1].x : vv[1].y, e < 2 ? vv[0].x : vv[0].y, sel);
-        w.y = __builtin_amdgcn_perm(e < 2 ? vv[3].x : vv[3].y, e < 2 ? vv[2].x : vv[2].y, sel);
-        w.z = __builtin_amdgcn_perm(e < 2 ? vv[5].x : vv[5].y, e < 2 ? vv[4].x : vv[4].y, sel);
-        w.w = __builtin_amdgcn_perm(e < 2 ? vv[7].x : vv[7].y, e < 2 ? vv[6].x : vv[6].y, sel);
-        acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pb, acc[e], 0, 0, 0);
-      }
-    }
+    tile_pv(lds_v, s, half, col, acc);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }
@@ -245,32 +140,9 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
       p.cand_ml[slot * 64 + lane] = mc_run;
       p.cand_ml[slot * 64 + 32 + lane] = lc_tot;
     }
-    if (p.n_split == 1) {
-      const float inv = 1.f / l_tot;
-      char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
-        bf16x4 o4;
-        o4[0] = (__bf16)(acc[0][i] * inv);
-        o4[1] = (__bf16)(acc[1][i] * inv);
-        o4[2] = (__bf16)(acc[2][i] * inv);
-        o4[3] = (__bf16)(acc[3][i] * inv);
-        *reinterpret_cast<bf16x4*>(op + mrow * 8) = o4;
-      }
-    } else {
-      float* po = p.part_o + (slot * 32 + col) * 128;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
-        const f32x4 o4 = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-        *reinterpret_cast<f32x4*>(po + mrow * 4) = o4;
-      }
-      if (lane < 32) {
-        p.part_ml[slot * 64 + lane] = m_run;
-        p.part_ml[slot * 64 + 32 + lane] = l_tot;
-      }
-    }
+    write_wave_result(acc, m_run, l_tot, lane, half, col, p.n_split == 1,
+                      (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr), p.part_o + (slot * 32 + col) * 128,
+                      p.part_ml + slot * 64);
     return;
   }
 

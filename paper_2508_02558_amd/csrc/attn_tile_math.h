@@ -1,0 +1,184 @@
+// Per-tile arithmetic shared by the bf16 MFMA attention kernels: one wavefront, 32 query rows of
+// one head, one 32-key tile of K and V in LDS (padded layout of mfma_tile.h).
+//
+// Fragment conventions (v_mfma_f32_32x32x16_bf16): lane = (col = lane % 32, half = lane / 32).
+//   logits^T = K_tile Q^T: K rows are the A operand, Q^T the B operand; register i of a lane is key
+//   8*(i/4) + 4*half + i%4 of the tile for query row `col`, so softmax row reductions are in-lane
+//   plus one exchange between the two halves.
+//   O^T += V_tile^T P^T: P^T (registers 8*step .. 8*step+7 of the logits, as bf16) is the B operand;
+//   V is read from LDS as 8-byte pieces of four head-dim columns and regrouped with v_perm so that
+//   MFMA e (0..3) produces columns 4m+e, m = 8*(i/4) + 4*half + i%4.
+#pragma once
+
+#include "mfma_tile.h"
+
+namespace sdllm {
+
+// Q^T fragments of query row `col` (16-byte pieces of the row, straight from global memory).
+__device__ __forceinline__ void load_q_frags(const char* q_row, int half, bf16x8 (&qf)[8]) {
+  const u32x4* qp = reinterpret_cast<const u32x4*>(q_row);
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const u32x4 raw = qp[t * 2 + half];
+    qf[t] = __builtin_bit_cast(bf16x8, raw);
+  }
+}
+
+// Raw logits of one tile (unscaled; keys >= rows become -inf).  Returns the row max over the tile
+// in the scaled log2 domain (scale_log2 > 0), already exchanged between the halves.
+__device__ __forceinline__ float tile_logits(const uint8_t* lds_k, const bf16x8 (&qf)[8], int rows, float scale_log2,
+                                             int half, int col, f32x16& s) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(lds_k + tile_off(col, kk * 2 + half));
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s, 0, 0, 0);
+  }
+  if (rows < kTileKeys) {   // only the last tile of a segment is ragged (wave-uniform)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key = half * 4 + (i >> 2) * 8 + (i & 3);
+      s[i] = key < rows ? s[i] : -INFINITY;
+    }
+  }
+  float m_loc = s[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) m_loc = fmaxf(m_loc, s[i]);
+  m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
+  return m_loc * scale_log2;
+}
+
+// Softmax numerators of one tile against a per-row reference m_ref that only moves when some row's
+// tile max exceeds it by more than kRescaleSlack (log2 units): s becomes exp2(scale*s - m_ref), which
+// is then at most 2^kRescaleSlack instead of at most 1.  Any common reference gives the same
+// quotient sum(p v)/sum(p); moving it rarely saves rescaling the 64 accumulator registers on almost
+// every tile.  l_run only covers the keys this half-lane holds; the halves are added at the end.
+constexpr float kRescaleSlack = 8.f;
+
+__device__ __forceinline__ void tile_softmax(f32x16& s, float m_loc, float scale_log2, float& m_ref, float& l_run,
+                                             f32x16 (&acc)[4]) {
+  if (__ballot(m_loc > m_ref + kRescaleSlack) != 0) {   // wave-uniform; always taken on a wave's first tile
+    const float m_new = fmaxf(m_ref, m_loc);
+    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // exp2(-inf) = 0 on the first tile
+    m_ref = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[e][i] *= alpha;
+  }
+  float l_loc = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    s[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], scale_log2, -m_ref));
+    l_loc += s[i];
+  }
+  l_run += l_loc;
+}
+
+// O^T[col 4m+e, query] += V_tile^T P^T, 16 keys per MFMA step.
+__device__ __forceinline__ void tile_pv(const uint8_t* lds_v, const f32x16& s, int half, int col, f32x16 (&acc)[4]) {
+#pragma unroll
+  for (int step = 0; step < 2; ++step) {
+    bf16x8 pb;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pb[j] = (__bf16)s[step * 8 + j];
+    u32x2 vv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int key_local = step * 16 + (j >> 2) * 8 + half * 4 + (j & 3);
+      vv[j] = *reinterpret_cast<const u32x2*>(lds_v + tile_off(key_local, col >> 1) + ((col & 1) << 3));
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      u32x4 w;
+      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+      w.x = __builtin_amdgcn_perm(e < 2 ? vv[1].x : vv[1].y, e < 2 ? vv[0].x : vv[0].y, sel);
+      w.y = __builtin_amdgcn_perm(e < 2 ? vv[3].x : vv[3].y, e < 2 ? vv[2].x : vv[2].y, sel);
+      w.z = __builtin_amdgcn_perm(e < 2 ? vv[5].x : vv[5].y, e < 2 ? vv[4].x : vv[4].y, sel);
+      w.w = __builtin_amdgcn_perm(e < 2 ? vv[7].x : vv[7].y, e < 2 ? vv[6].x : vv[6].y, sel);
+      acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pb, acc[e], 0, 0, 0);
+    }
+  }
+}
+
+// One wave owns the complete result of a head (or of a key split of it): normalised bf16 rows to
+// `out_row` (n_split == 1) or fp32 numerators + (max, sum) to the split-KV partial buffers.
+__device__ __forceinline__ void write_wave_result(const f32x16 (&acc)[4], float m_run, float l_tot, int lane, int half,
+                                                  int col, bool final_out, char* out_row, float* part_o_row,
+                                                  float* part_ml_slot) {
+  if (final_out) {
+    const float inv = 1.f / l_tot;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
+      bf16x4 o4;
+      o4[0] = (__bf16)(acc[0][i] * inv);
+      o4[1] = (__bf16)(acc[1][i] * inv);
+      o4[2] = (__bf16)(acc[2][i] * inv);
+      o4[3] = (__bf16)(acc[3][i] * inv);
+      *reinterpret_cast<bf16x4*>(out_row + mrow * 8) = o4;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
+      const f32x4 o4 = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+      *reinterpret_cast<f32x4*>(part_o_row + mrow * 4) = o4;
+    }
+    if (lane < 32) {
+      part_ml_slot[lane] = m_run;
+      part_ml_slot[32 + lane] = l_tot;
+    }
+  }
+}
+
+// Two key segments, tiles never straddling them: segment 0 contributes ceil(n0/32) tiles, segment 1
+// the rest.  A tile has one wave-uniform base pointer and row count, and K and V (which share
+// strides) are addressed with the same per-lane 32-bit byte offsets.
+struct TileSrc {
+  const char* k;
+  const char* v;
+  int rows;        // valid keys in this tile (1..32)
+};
+
+struct SegPtrs {
+  const char* k0; const char* v0; uint32_t r0;   // byte stride per row, segment 0
+  const char* k1; const char* v1; uint32_t r1;
+  int n0, n1, tiles0;
+};
+
+__device__ __forceinline__ SegPtrs seg_ptrs(const AttnParams& p, int b, int g, bool two_segments) {
+  SegPtrs sp;
+  sp.n0 = p.seg[0].n;
+  sp.n1 = two_segments ? p.seg[1].n : 0;
+  sp.tiles0 = (sp.n0 + kTileKeys - 1) / kTileKeys;
+  sp.r0 = (uint32_t)(p.seg[0].sr * 2);
+  sp.r1 = (uint32_t)(p.seg[1].sr * 2);
+  sp.k0 = (const char*)p.seg[0].k + 2 * (b * p.seg[0].sb + g * p.seg[0].sh);
+  sp.v0 = (const char*)p.seg[0].v + 2 * (b * p.seg[0].sb + g * p.seg[0].sh);
+  sp.k1 = (const char*)p.seg[1].k + 2 * (b * p.seg[1].sb + g * p.seg[1].sh);
+  sp.v1 = (const char*)p.seg[1].v + 2 * (b * p.seg[1].sb + g * p.seg[1].sh);
+  return sp;
+}
+
+__device__ __forceinline__ TileSrc tile_src(const SegPtrs& sp, int tile, uint32_t& row_stride) {
+  TileSrc ts;
+  if (tile < sp.tiles0) {
+    const int first = tile * kTileKeys;
+    ts.k = sp.k0 + (size_t)first * sp.r0;
+    ts.v = sp.v0 + (size_t)first * sp.r0;
+    ts.rows = min(kTileKeys, sp.n0 - first);
+    row_stride = sp.r0;
+  } else {
+    const int first = (tile - sp.tiles0) * kTileKeys;
+    ts.k = sp.k1 + (size_t)first * sp.r1;
+    ts.v = sp.v1 + (size_t)first * sp.r1;
+    ts.rows = min(kTileKeys, sp.n1 - first);
+    row_stride = sp.r1;
+  }
+  return ts;
+}
+
+}  // namespace sdllm

@@ -222,3 +222,30 @@ def test_scores_match_oracle_values():
             else:
                 np.testing.assert_allclose(sg, score_orc, rtol=0, atol=2e-5)
                 np.testing.assert_allclose(pg, pooled_orc, rtol=0, atol=2e-5)
+
+
+def test_grouped_query_kernel_at_large_batch():
+    # B*Hq >= 512 switches sdllm_sparse_attn / the dense step to the shared-tile grouped-query kernel
+    _note("[case] grouped-query shared-tile kernel")
+    w = wl.WORKLOADS["dream7b_gqa"].scaled(batch=19, prompt=300, gen=64)     # 532 query heads, ragged tiles
+    inp = wl.make_block_inputs(w, n_steps=3, device=DEV)
+    shape = U.shape_for(w)
+    gl = U.GpuLayer(shape, DEV)
+    o, b = inp["block_off"], w.block
+    q1 = inp["q"][1].contiguous()
+    assert gl.block_step(1, 1, q1, inp["k_full"], inp["v_full"]) == 1
+    bs = [0, 7, 18]
+    U.assert_close(gl.out[bs], U.oracle_attention_batch(q1[bs], inp["k_full"][bs], inp["v_full"][bs]), "bf16", "dense gqa")
+    q2, kb, vb = inp["q"][2].contiguous(), inp["k_blk"][2].contiguous(), inp["v_blk"][2].contiguous()
+    assert gl.block_step(2, 1, q2, kb, vb) == 2
+    kt = gl.k_total
+    ref = U.oracle_attention_batch(q2[bs], torch.cat([gl.k_cache[bs, :, :kt], kb[bs]], 2),
+                                   torch.cat([gl.v_cache[bs, :, :kt], vb[bs]], 2))
+    U.assert_close(gl.out[bs], ref, "bf16", "sparse gqa")
+    for G, Hkv in ((2, 3), (8, 1)):
+        w2 = w.scaled(batch=600 // (G * Hkv) + 1, n_q_heads=G * Hkv, n_kv_heads=Hkv, prompt=70, gen=64)
+        inp2 = wl.make_block_inputs(w2, n_steps=1, device=DEV)
+        gl2 = U.GpuLayer(U.shape_for(w2), DEV)
+        q = inp2["q"][0].contiguous()
+        gl2.block_step(0, 1, q, inp2["k_full"], inp2["v_full"])
+        U.assert_close(gl2.out[:2], U.oracle_attention_batch(q[:2], inp2["k_full"][:2], inp2["v_full"][:2]), "bf16", f"G={G}")
