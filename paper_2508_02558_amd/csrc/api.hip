@@ -127,13 +127,15 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   } else if (pl.mfma) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int heads = s.batch * s.n_q_heads;
-    // aim at 8 waves on every CU, never more waves than tiles
-    int waves_per_head = (kNumCUs * kMaxWavesPerWg + heads - 1) / heads;
-    if (waves_per_head > tiles) waves_per_head = tiles;
-    if (waves_per_head < 1) waves_per_head = 1;
-    pl.waves = waves_per_head < kMaxWavesPerWg ? waves_per_head : kMaxWavesPerWg;
-    int n_split = (waves_per_head + pl.waves - 1) / pl.waves;
+    // Split the keys of a head over workgroups only while the grid is small: about 192 workgroups
+    // in total and at least two tiles per wave were the fastest plans measured on MI355X (a split
+    // costs fp32 partials and a second launch).  From 192 heads on there is one workgroup per head.
+    int n_split = (192 + heads / 2) / heads;
+    const int max_split = tiles / (2 * kMaxWavesPerWg);
+    if (n_split > max_split) n_split = max_split;
+    if (n_split < 1) n_split = 1;
     pl.tiles_per_split = (tiles + n_split - 1) / n_split;
+    pl.waves = pl.tiles_per_split < kMaxWavesPerWg ? pl.tiles_per_split : kMaxWavesPerWg;
     pl.n_split = (tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;   // no empty split
     if (pl.n_split > 1) {
       const size_t slots = (size_t)heads * pl.n_split;

@@ -29,7 +29,10 @@ size_t attn_mfma_lds_bytes(int waves) { return (size_t)waves * kWaveLds; }
 // profile, which keeps sparse and dense launches apart.
 // STATS (dense launches of the cache-update step only): also accumulate each query row's (max, sum)
 // over the candidate keys, so the scoring pass that follows need not stream K for them again.
-template <int NSEG, bool STATS>
+// DEEP: prefetch K and V of the next tile together (one memory latency per tile instead of two, twice
+// the bytes in flight).  Chosen for small grids, which are latency-bound; large grids saturate HBM and
+// run faster with the shallower alternating scheme.
+template <int NSEG, bool STATS, bool DEEP>
 __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   const int lane = threadIdx.x & 63;
@@ -70,24 +73,36 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   float l_run = 0.f;         // running row sum over the keys this half-lane has seen
   float mc_run = -INFINITY, lc_run = 0.f;   // the same over candidate keys only (STATS)
 
-  // One staging register set, used alternately for the K and the V tile: a wave keeps exactly one
-  // 8 KB tensor tile in flight (64 KB per CU with 8 waves).  Measured on MI355X, a streaming read
-  // is fastest with 32-64 KB outstanding per CU and loses ~5 % at 128 KB, so K(t+1) flies under the
-  // PV product of tile t and V(t) under its logits/softmax instead of both being prefetched together.
-  u32x4 reg[8];
+  // Shallow scheme: one staging register set, used alternately for the K and the V tile, so a wave
+  // keeps exactly one 8 KB tensor tile in flight (64 KB per CU with 8 waves).  Measured on MI355X, a
+  // streaming read is fastest with 32-64 KB outstanding per CU and loses ~5 % at 128 KB, so K(t+1)
+  // flies under the PV product of tile t and V(t) under its logits/softmax.
+  u32x4 reg[8], reg2[DEEP ? 8 : 1];
   int t = t_begin + wave;
   uint32_t stride = 0;
   TileSrc ts{};
   if (t < t_end) {
     ts = tile_src(sp, t, stride);
     load_rows(ts.k, ts.rows, stride, lane, reg);
+    if (DEEP) load_rows(ts.v, ts.rows, stride, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
   }
 
   for (; t < t_end; t += nw) {
-    store_rows(lds_k, lane, reg);
-    wave_lds_sync();
-    load_rows(ts.v, ts.rows, stride, lane, reg);   // V(t) flies during the logits and the softmax
     const int rows = ts.rows;
+    const int tn = t + nw;
+    store_rows(lds_k, lane, reg);
+    if (DEEP) {
+      store_rows(lds_v, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
+      wave_lds_sync();
+      if (tn < t_end) {                              // both tensors of tile t+1 fly during tile t
+        ts = tile_src(sp, tn, stride);
+        load_rows(ts.k, ts.rows, stride, lane, reg);
+        load_rows(ts.v, ts.rows, stride, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
+      }
+    } else {
+      wave_lds_sync();
+      load_rows(ts.v, ts.rows, stride, lane, reg);   // V(t) flies during the logits and the softmax
+    }
 
     // logits^T[key, query] = K_tile Q^T (raw), row max in the scaled log2 domain
     f32x16 s;
@@ -117,12 +132,13 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     }
     tile_softmax(s, m_loc, p.scale_log2, m_run, l_run, acc);
 
-    store_rows(lds_v, lane, reg);
-    wave_lds_sync();
-    const int tn = t + nw;
-    if (tn < t_end) {                                // K(t+1) flies during the PV product
-      ts = tile_src(sp, tn, stride);
-      load_rows(ts.k, ts.rows, stride, lane, reg);
+    if (!DEEP) {
+      store_rows(lds_v, lane, reg);
+      wave_lds_sync();
+      if (tn < t_end) {                              // K(t+1) flies during the PV product
+        ts = tile_src(sp, tn, stride);
+        load_rows(ts.k, ts.rows, stride, lane, reg);
+      }
     }
 
     tile_pv(lds_v, s, half, col, acc);
@@ -221,18 +237,26 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   }
 }
 
-template <int NSEG, bool STATS>
-static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
+template <int NSEG, bool STATS, bool DEEP>
+static hipError_t launch_variant(const AttnParams& p, hipStream_t s) {
   const int nwg = p.batch * p.hq * p.n_split;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel<NSEG, STATS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel<NSEG, STATS, DEEP>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(kMaxWavesPerWg));
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((attn_mfma_bf16_kernel<NSEG, STATS>), dim3(nwg), dim3(p.waves * kWave), attn_mfma_lds_bytes(p.waves), s, p);
+  hipLaunchKernelGGL((attn_mfma_bf16_kernel<NSEG, STATS, DEEP>), dim3(nwg), dim3(p.waves * kWave),
+                     attn_mfma_lds_bytes(p.waves), s, p);
   return hipGetLastError();
+}
+
+template <int NSEG, bool STATS>
+static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
+  // at most half the CUs busy: latency-bound, take the deep prefetch
+  const bool deep = p.batch * p.hq * p.n_split <= kNumCUs / 2;
+  return deep ? launch_variant<NSEG, STATS, true>(p, s) : launch_variant<NSEG, STATS, false>(p, s);
 }
 
 hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s) {
