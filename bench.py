@@ -82,6 +82,8 @@ def main() -> int:
     ap.add_argument("--workload", default="llada8b_sweep")
     ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the block as a captured HIP graph (removes host launch cost; matters for batch-1 shapes)")
     ap.add_argument("--cpu-batch", type=int, default=8, help="batch elements the oracle baseline runs")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -159,18 +161,46 @@ def main() -> int:
                 e1.record()
                 sparse_events.append((e0, e1))
 
-    for _ in range(args.warmup):
+    for _ in range(max(1, args.warmup) if args.graph else args.warmup):
         run_block(False)
     torch.cuda.synchronize()
+    if args.graph:
+        # the library only enqueues kernels on the given stream (no allocation, no memset, no sync),
+        # so a whole block records into one graph; the sparse sweep is captured separately to time it
+        side = torch.cuda.Stream()
+        g_block, g_sparse = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_block, stream=side):
+            run_block(False)
+        t_sparse = next(t for t in range(T) if states[t] == B.SDLLM_STATE_REUSE)
+        with torch.cuda.graph(g_sparse, stream=side):
+            for st in layers:
+                B.sdllm_block_step(shape, t_sparse, 1, st["q"][t_sparse], st["k_blk"][t_sparse], st["v_blk"][t_sparse],
+                                   st["idx"], st["k_cache"], st["v_cache"], st["out"], ws)
+        g_block.replay()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        run_block(True)
+        if args.graph:
+            g_block.replay()
+        else:
+            run_block(True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    if args.graph:
+        reps = 10
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g_sparse.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        sparse_events = None
+        sparse_ms = [e0.elapsed_time(e1) / reps]
+    else:
+        sparse_ms = [a.elapsed_time(bb) for a, bb in sparse_events]
 
     elapsed = t1 - t0
     calls = args.steps * T * n_layers
-    sparse_ms = [a.elapsed_time(bb) for a, bb in sparse_events]
     sparse_launch_us = 1e3 * sum(sparse_ms) / (len(sparse_ms) * n_layers) if sparse_ms else float("nan")
     bytes_sparse = attn_bytes(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, k_total + b, b, esize)
     achieved = bytes_sparse / (sparse_launch_us * 1e-6) / 1e9 if sparse_ms else float("nan")
@@ -231,6 +261,7 @@ def main() -> int:
                                f"d={w.head_dim}), prompt {w.prompt}, gen {w.gen}, block {b}, {T} steps/block, "
                                f"r={w.retention}, pool {w.pool_kernel}; one step = one decoding block through all layers",
                    "block_steps_per_step": T * n_layers, "retained_per_head": k_total},
+        "launch_mode": "hip graph replay" if args.graph else "eager launches",
         "tokens_per_s_attention_path": w.batch * b * args.steps / elapsed,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),

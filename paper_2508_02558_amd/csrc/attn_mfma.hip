@@ -32,7 +32,9 @@ size_t attn_mfma_lds_bytes(int waves) { return (size_t)waves * kWaveLds; }
 // DEEP: prefetch K and V of the next tile together (one memory latency per tile instead of two, twice
 // the bytes in flight).  Chosen for small grids, which are latency-bound; large grids saturate HBM and
 // run faster with the shallower alternating scheme.
-template <int NSEG, bool STATS, bool DEEP>
+// SHARED_KV: the G query heads of a KV group run as separate workgroups (grouped-query attention on
+// a small grid); their K/V reads are then plain loads so that the siblings hit in L2.
+template <int NSEG, bool STATS, bool DEEP, bool SHARED_KV>
 __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   const int lane = threadIdx.x & 63;
@@ -83,8 +85,8 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   TileSrc ts{};
   if (t < t_end) {
     ts = tile_src(sp, t, stride);
-    load_rows(ts.k, ts.rows, stride, lane, reg);
-    if (DEEP) load_rows(ts.v, ts.rows, stride, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
+    load_rows<!SHARED_KV>(ts.k, ts.rows, stride, lane, reg);
+    if (DEEP) load_rows<!SHARED_KV>(ts.v, ts.rows, stride, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
   }
 
   for (; t < t_end; t += nw) {
@@ -96,12 +98,12 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
       wave_lds_sync();
       if (tn < t_end) {                              // both tensors of tile t+1 fly during tile t
         ts = tile_src(sp, tn, stride);
-        load_rows(ts.k, ts.rows, stride, lane, reg);
-        load_rows(ts.v, ts.rows, stride, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
+        load_rows<!SHARED_KV>(ts.k, ts.rows, stride, lane, reg);
+        load_rows<!SHARED_KV>(ts.v, ts.rows, stride, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
       }
     } else {
       wave_lds_sync();
-      load_rows(ts.v, ts.rows, stride, lane, reg);   // V(t) flies during the logits and the softmax
+      load_rows<!SHARED_KV>(ts.v, ts.rows, stride, lane, reg);   // V(t) flies during the logits and the softmax
     }
 
     // logits^T[key, query] = K_tile Q^T (raw), row max in the scaled log2 domain
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
       wave_lds_sync();
       if (tn < t_end) {                              // K(t+1) flies during the PV product
         ts = tile_src(sp, tn, stride);
-        load_rows(ts.k, ts.rows, stride, lane, reg);
+        load_rows<!SHARED_KV>(ts.k, ts.rows, stride, lane, reg);
       }
     }
 
@@ -237,17 +239,17 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   }
 }
 
-template <int NSEG, bool STATS, bool DEEP>
+template <int NSEG, bool STATS, bool DEEP, bool SHARED_KV>
 static hipError_t launch_variant(const AttnParams& p, hipStream_t s) {
   const int nwg = p.batch * p.hq * p.n_split;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel<NSEG, STATS, DEEP>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel<NSEG, STATS, DEEP, SHARED_KV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(kMaxWavesPerWg));
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((attn_mfma_bf16_kernel<NSEG, STATS, DEEP>), dim3(nwg), dim3(p.waves * kWave),
+  hipLaunchKernelGGL((attn_mfma_bf16_kernel<NSEG, STATS, DEEP, SHARED_KV>), dim3(nwg), dim3(p.waves * kWave),
                      attn_mfma_lds_bytes(p.waves), s, p);
   return hipGetLastError();
 }
@@ -256,7 +258,11 @@ template <int NSEG, bool STATS>
 static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
   // at most half the CUs busy: latency-bound, take the deep prefetch
   const bool deep = p.batch * p.hq * p.n_split <= kNumCUs / 2;
-  return deep ? launch_variant<NSEG, STATS, true>(p, s) : launch_variant<NSEG, STATS, false>(p, s);
+  if (p.group > 1) {
+    if (STATS) return hipErrorInvalidValue;   // fused statistics exist for group == 1 only
+    return deep ? launch_variant<NSEG, false, true, true>(p, s) : launch_variant<NSEG, false, false, true>(p, s);
+  }
+  return deep ? launch_variant<NSEG, STATS, true, false>(p, s) : launch_variant<NSEG, STATS, false, false>(p, s);
 }
 
 hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s) {

@@ -249,3 +249,34 @@ def test_grouped_query_kernel_at_large_batch():
         q = inp2["q"][0].contiguous()
         gl2.block_step(0, 1, q, inp2["k_full"], inp2["v_full"])
         U.assert_close(gl2.out[:2], U.oracle_attention_batch(q[:2], inp2["k_full"][:2], inp2["v_full"][:2]), "bf16", f"G={G}")
+
+
+def test_block_step_replays_identically_from_a_hip_graph():
+    # the library only enqueues kernels (no allocation, no memset, no host sync), so a block step can
+    # be captured; every replay must reproduce the eager result, with eager work in between
+    _note("[case] HIP graph capture / replay")
+    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=8, n_kv_heads=8, prompt=700, gen=96)
+    inp = wl.make_block_inputs(w, n_steps=3, device=DEV)
+    shape = U.shape_for(w)
+    gl = U.GpuLayer(shape, DEV)
+    q1, q2 = inp["q"][1].contiguous(), inp["q"][2].contiguous()
+    kb, vb = inp["k_blk"][2].contiguous(), inp["v_blk"][2].contiguous()
+    gl.block_step(1, 1, q1, inp["k_full"], inp["v_full"])
+    eager_idx, eager_kc = gl.idx.clone(), gl.k_cache.clone()
+    gl.block_step(2, 1, q2, kb, vb)
+    eager_out = gl.out.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        B.sdllm_block_step(shape, 1, 1, q1, inp["k_full"], inp["v_full"], gl.idx, gl.k_cache, gl.v_cache, gl.out, gl.ws)
+        B.sdllm_block_step(shape, 2, 1, q2, kb, vb, gl.idx, gl.k_cache, gl.v_cache, gl.out, gl.ws)
+    for rep in range(3):
+        gl.idx.fill_(-1); gl.k_cache.zero_(); gl.out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(gl.idx, eager_idx), rep
+        assert torch.equal(gl.k_cache, eager_kc), rep
+        assert torch.equal(gl.out, eager_out), rep
+        # eager work between replays
+        gl.block_step(0, 1, q1, inp["k_full"], inp["v_full"])
