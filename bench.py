@@ -81,6 +81,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="llada8b_sweep")
     ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (batch sweep)")
+    ap.add_argument("--block-index", type=int, default=0, help="which decoding block of the generation to run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="replay the block as a captured HIP graph (removes host launch cost; matters for batch-1 shapes)")
@@ -101,13 +103,15 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     w = wl.WORKLOADS[args.workload]
+    if args.batch > 0:
+        w = w.scaled(batch=args.batch)
     n_layers = args.layers if args.layers > 0 else w.n_layers
     # one-layer workloads are rotated over 32 distinct buffer sets so that re-reads cannot be
     # served by the 256 MB last-level cache
     if n_layers == 1 and args.layers == 0:
         n_layers = 32
     T = w.steps_per_block
-    o, b = w.block_off(0), w.block
+    o, b = w.block_off(args.block_index), w.block
     esize = 2 if w.dtype == "bf16" else 4
     shape = B.make_shape(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
                          seq_len=w.seq_len, block_off=o, block_len=b,
@@ -123,7 +127,7 @@ def main() -> int:
     layers = []
     inp0_host = None
     for layer in range(n_layers):
-        inp = wl.make_block_inputs(w, layer, 0, T, device=dev)
+        inp = wl.make_block_inputs(w, layer, args.block_index, T, device=dev)
         td = w.torch_dtype
         st = dict(k_full=inp["k_full"], v_full=inp["v_full"], q=inp["q"], k_blk=inp["k_blk"], v_blk=inp["v_blk"],
                   k_cache=torch.zeros(w.batch, w.n_kv_heads, max(1, k_total), w.head_dim, dtype=td, device=dev),
@@ -259,7 +263,8 @@ def main() -> int:
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: {n_layers} layers x (B={w.batch}, Hq={w.n_q_heads}, Hkv={w.n_kv_heads}, "
                                f"d={w.head_dim}), prompt {w.prompt}, gen {w.gen}, block {b}, {T} steps/block, "
-                               f"r={w.retention}, pool {w.pool_kernel}; one step = one decoding block through all layers",
+                               f"r={w.retention}, pool {w.pool_kernel}, block index {args.block_index}; one step = one decoding block "
+                               f"through all layers",
                    "block_steps_per_step": T * n_layers, "retained_per_head": k_total},
         "launch_mode": "hip graph replay" if args.graph else "eager launches",
         "tokens_per_s_attention_path": w.batch * b * args.steps / elapsed,

@@ -83,6 +83,12 @@ WORKLOADS: Dict[str, Workload] = {
                               0.5, 3, 32, 0.02, 3.0, 0, 0.5, 0.9),
     "dream_long": Workload("dream_long", 4, 1, 28, 4, 128, "bf16", 32768, 512, 32, 32,
                            0.25, 3, 1, 0.01, 3.0, 64, 0.5, 0.9),
+    # second shape family of the paper's runs: 512 denoising steps for a 512-token generation
+    # (16 blocks of 32, still 32 steps per block) after a 4k input (HumanEval / LongBench settings)
+    "llada8b_gen512": Workload("llada8b_gen512", 5, 8, 32, 32, 128, "bf16", 4096, 512, 32, 32,
+                               0.5, 3, 32, 0.02, 3.0, 0, 0.5, 0.9),
+    "dream7b_gen512": Workload("dream7b_gen512", 6, 8, 28, 4, 128, "bf16", 4096, 512, 32, 32,
+                               0.5, 3, 28, 0.02, 3.0, 0, 0.5, 0.9),
 }
 WORKLOAD_LIST: List[Workload] = sorted(WORKLOADS.values(), key=lambda w: w.index)
 

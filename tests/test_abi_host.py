@@ -123,10 +123,10 @@ def test_workspace_sizes(lib):
     for op in (B.SDLLM_OP_SCORE_SELECT, B.SDLLM_OP_COMPACT_KV, B.SDLLM_OP_SPARSE_ATTN, B.SDLLM_OP_BLOCK_STEP):
         assert B.sdllm_workspace_bytes(s, op, 64) >= 256
     # split-KV partials of the MFMA path: a batch-1 LLaDA-shaped call needs room for them
-    big = B.make_shape(batch=1, n_q_heads=32, n_kv_heads=32, head_dim=128, seq_len=1280, block_off=1024,
+    big = B.make_shape(batch=1, n_q_heads=32, n_kv_heads=32, head_dim=128, seq_len=4352, block_off=4096,
                        block_len=32, dtype=B.SDLLM_BF16)
     kt, _, _ = B.sdllm_retained_count(big)
-    assert kt == 624
+    assert kt == 2160
     assert B.sdllm_workspace_bytes(big, B.SDLLM_OP_SPARSE_ATTN, kt) > 32 * 32 * 128 * 4
     assert B.sdllm_workspace_bytes(big, B.SDLLM_OP_BLOCK_STEP) >= B.sdllm_workspace_bytes(big, B.SDLLM_OP_SCORE_SELECT)
     with pytest.raises(B.SdllmError):

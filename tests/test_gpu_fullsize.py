@@ -78,3 +78,30 @@ def test_llada8b_sweep_layer_full_size():
 def test_dream_long_full_size():
     # 28 query / 4 KV heads, prompt 32768, r = 0.25: top-k over 33 248 candidates per row
     _full_block(wl.WORKLOADS["dream_long"], samples=[(0, 0), (0, 3)])
+
+
+def test_gen512_late_block_full_size():
+    # 512-token generation after a 4k input: block 13 of 16 has a 4512-token prefix and a 64-token suffix
+    w = wl.WORKLOADS["llada8b_gen512"].scaled(batch=2)
+    print(f"[case] {w.name} block 13", flush=True)
+    inp = wl.make_block_inputs(w, 0, 13, 3, device=DEV)
+    o, b = inp["block_off"], w.block
+    assert o == 4096 + 13 * 32
+    shape = U.shape_for(w, 13)
+    gl = U.GpuLayer(shape, DEV)
+    q1 = inp["q"][1]
+    assert gl.block_step(1, 1, q1, inp["k_full"], inp["v_full"]) == 1
+    kt = gl.k_total
+    assert kt == (o + 1) // 2 + 32
+    for (bi, g) in [(0, 0), (1, 31)]:
+        i_orc, pooled_orc, _ = orc.score_select(wl.to_f64(q1[bi, g:g + 1]), wl.to_f64(inp["k_full"][bi, g:g + 1]), o, b,
+                                                w.retention, w.pool_kernel)
+        U.compare_index_rows(gl.idx[bi, g, :kt].cpu().numpy().astype(np.int64), i_orc[0], pooled_orc[0], w.seq_len, o, b,
+                             U.ranked_segments(shape))
+    q2, kb, vb = inp["q"][2], inp["k_blk"][2], inp["v_blk"][2]
+    assert gl.block_step(2, 1, q2, kb, vb) == 2
+    for (bi, g) in [(0, 5), (1, 30)]:
+        kc = torch.cat([gl.k_cache[bi, g:g + 1, :kt], kb[bi, g:g + 1]], 1)
+        vc = torch.cat([gl.v_cache[bi, g:g + 1, :kt], vb[bi, g:g + 1]], 1)
+        U.assert_close(gl.out[bi, g:g + 1], orc.attention(wl.to_f64(q2[bi, g:g + 1]), wl.to_f64(kc), wl.to_f64(vc)), "bf16",
+                       f"sparse sample {(bi, g)}")

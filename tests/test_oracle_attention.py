@@ -218,6 +218,7 @@ def test_workload_shapes_and_determinism():
     sal = a["salient"].tolist()
     assert len(sal) == 4 and all(0 < p < 63 for p in sal) and min(np.diff(sal)) >= 3
     names = [x.name for x in wl.WORKLOAD_LIST]
-    assert names == ["tiny", "llada8b_layer", "dream7b_gqa", "llada8b_sweep", "dream_long"]
+    assert names[:5] == ["tiny", "llada8b_layer", "dream7b_gqa", "llada8b_sweep", "dream_long"]
+    assert wl.WORKLOADS["llada8b_gen512"].n_blocks == 16
     w4 = wl.WORKLOADS["dream_long"]
     assert w4.seq_len - w4.block == 33248
