@@ -177,6 +177,20 @@ int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int3
                          const void* k_in, const void* v_in, int32_t* idx, void* k_cache, void* v_cache, void* out,
                          void* ws, size_t ws_bytes, void* stream, int32_t* state_out);
 
+/*
+ * Full bidirectional attention of ALL L positions (Sec. 3.1: the mask predictor recomputes the whole
+ * sequence; cache_state 0 and 1 of the cache-management appendix run it for the rows outside the
+ * current block, whose block rows sdllm_block_step returns):
+ *   out[b,h,i,:] = sum_j softmax_j(scale * <q[b,h,i], k[b,g(h),j]>) v[b,g(h),j],  i, j in [0, L), no mask.
+ * q_full/out_full are [B,Hq,L,d] with element strides {batch, head, row} given by q_full_stride /
+ * out_full_stride (host pointers to 3 values); k_full/v_full [B,Hkv,L,d] use shape->kv_stride.
+ * Only batch, head counts, head_dim, seq_len, dtype, softmax_scale and kv_stride of `shape` are read
+ * besides the usual validity checks.  No workspace.
+ */
+int32_t sdllm_dense_attn(const sdllm_shape_t* shape, const void* q_full, const int64_t* q_full_stride,
+                         const void* k_full, const void* v_full, void* out_full, const int64_t* out_full_stride,
+                         void* stream);
+
 #ifdef __cplusplus
 }
 #endif

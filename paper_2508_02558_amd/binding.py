@@ -28,7 +28,7 @@ SDLLM_OP_SCORE_SELECT, SDLLM_OP_COMPACT_KV, SDLLM_OP_SPARSE_ATTN, SDLLM_OP_BLOCK
 
 EXPORTED = ("sdllm_error_string", "sdllm_version", "sdllm_retained_count", "sdllm_workspace_bytes",
             "sdllm_cache_state", "sdllm_score_select", "sdllm_compact_kv", "sdllm_sparse_attn",
-            "sdllm_block_step")
+            "sdllm_block_step", "sdllm_dense_attn")
 
 
 class sdllm_shape_t(ctypes.Structure):
@@ -83,6 +83,8 @@ def load() -> ctypes.CDLL:
     lib.sdllm_sparse_attn.argtypes = [shp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.sdllm_block_step.restype = i32
     lib.sdllm_block_step.argtypes = [shp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, i32p]
+    lib.sdllm_dense_attn.restype = i32
+    lib.sdllm_dense_attn.argtypes = [shp, vp, ctypes.POINTER(ctypes.c_int64), vp, vp, vp, ctypes.POINTER(ctypes.c_int64), vp]
     _lib = lib
     return lib
 
@@ -196,3 +198,10 @@ def sdllm_block_step(shape, step_in_block, delay, q_blk, k_in, v_in, idx, k_cach
                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream),
                                    ctypes.byref(st)), "sdllm_block_step")
     return st.value
+
+
+def sdllm_dense_attn(shape, q_full, k_full, v_full, out_full, stream=None) -> None:
+    qs = (ctypes.c_int64 * 3)(*strides_of(q_full))
+    os_ = (ctypes.c_int64 * 3)(*strides_of(out_full))
+    _check(load().sdllm_dense_attn(ctypes.byref(shape), _ptr(q_full), qs, _ptr(k_full), _ptr(v_full), _ptr(out_full), os_,
+                                   _stream(stream)), "sdllm_dense_attn")

@@ -45,7 +45,7 @@ Counts counts_of(const sdllm_shape_t& s) {
   return c;
 }
 
-bool strides_ok(const int64_t st[3], int esize) {
+bool strides_ok(const int64_t* st, int esize) {
   for (int i = 0; i < 3; ++i)
     if (st[i] < 0 || (st[i] * esize) % 16 != 0) return false;
   return true;
@@ -77,7 +77,7 @@ int32_t check_shape(const sdllm_shape_t* s) {
   return SDLLM_OK;
 }
 
-bool row_stride_ok(const int64_t st[3], int d) { return st[2] >= d; }
+bool row_stride_ok(const int64_t* st, int d) { return st[2] >= d; }
 
 float scale_of(const sdllm_shape_t& s) {
   return s.softmax_scale > 0.f ? s.softmax_scale : 1.0f / sqrtf((float)s.head_dim);
@@ -451,6 +451,47 @@ int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int3
                          w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts);
   if (st != SDLLM_OK) return st;
   return sdllm_compact_kv(shape, k_in, v_in, idx, k_cache, v_cache, stream);
+}
+
+int32_t sdllm_dense_attn(const sdllm_shape_t* shape, const void* q_full, const int64_t* q_full_stride,
+                         const void* k_full, const void* v_full, void* out_full, const int64_t* out_full_stride,
+                         void* stream) {
+  const int32_t st = check_shape(shape);
+  if (st != SDLLM_OK) return st;
+  const sdllm_shape_t& s = *shape;
+  if (!q_full || !k_full || !v_full || !out_full || !q_full_stride || !out_full_stride) return SDLLM_ERR_INVALID_ARG;
+  if (!aligned16(q_full) || !aligned16(k_full) || !aligned16(v_full) || !aligned16(out_full)) return SDLLM_ERR_INVALID_ARG;
+  const int es = elem_size(s.dtype);
+  if (!strides_ok(q_full_stride, es) || !strides_ok(out_full_stride, es) || !row_stride_ok(q_full_stride, s.head_dim) ||
+      !row_stride_ok(out_full_stride, s.head_dim) || !row_stride_ok(s.kv_stride, s.head_dim))
+    return SDLLM_ERR_INVALID_ARG;
+  const float scale_log2 = scale_of(s) * kLog2e;
+  hipError_t e;
+  if (s.dtype == SDLLM_BF16 && s.head_dim == 128 && seg_fits_u32(s.kv_stride[2], s.seq_len, 2)) {
+    DenseFullParams p{};
+    p.q = q_full; p.k = k_full; p.v = v_full; p.out = out_full;
+    p.q_sb = q_full_stride[0]; p.q_sh = q_full_stride[1]; p.q_sr = q_full_stride[2];
+    p.k_sb = s.kv_stride[0]; p.k_sh = s.kv_stride[1]; p.k_sr = s.kv_stride[2];
+    p.o_sb = out_full_stride[0]; p.o_sh = out_full_stride[1]; p.o_sr = out_full_stride[2];
+    p.batch = s.batch; p.hq = s.n_q_heads; p.hkv = s.n_kv_heads; p.group = s.n_q_heads / s.n_kv_heads;
+    p.seq_len = s.seq_len; p.d = s.head_dim;
+    p.scale_log2 = scale_log2;
+    e = launch_dense_full_mfma_bf16(p, (hipStream_t)stream);
+  } else {
+    // generic path: one wave per query row over a single key segment
+    AttnParams p{};
+    p.q = q_full; p.out = out_full;
+    p.seg[0] = KvSegment{k_full, v_full, s.kv_stride[0], s.kv_stride[1], s.kv_stride[2], s.seq_len};
+    p.seg[1] = KvSegment{nullptr, nullptr, 0, 0, 0, 0};
+    p.q_sb = q_full_stride[0]; p.q_sh = q_full_stride[1]; p.q_sr = q_full_stride[2];
+    p.o_sb = out_full_stride[0]; p.o_sh = out_full_stride[1]; p.o_sr = out_full_stride[2];
+    p.batch = s.batch; p.hq = s.n_q_heads; p.hkv = s.n_kv_heads; p.group = s.n_q_heads / s.n_kv_heads;
+    p.nq = s.seq_len; p.d = s.head_dim;
+    p.scale_log2 = scale_log2;
+    p.n_split = 1; p.waves = 1;
+    e = launch_attn_simple(p, s.dtype, (hipStream_t)stream);
+  }
+  return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
 }
 
 }  // extern "C"

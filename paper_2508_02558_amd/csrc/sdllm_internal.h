@@ -98,6 +98,19 @@ struct CompactParams {
   int32_t row_bytes;
 };
 
+// Full-sequence bidirectional attention: L query rows per head over all L keys.
+struct DenseFullParams {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+  int64_t q_sb, q_sh, q_sr;
+  int64_t k_sb, k_sh, k_sr;
+  int64_t o_sb, o_sh, o_sr;
+  int32_t batch, hq, hkv, group, seq_len, d;
+  float scale_log2;
+};
+
 // kernel launchers (each returns hipGetLastError() after its launches)
 hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s);
 hipError_t launch_attn_gqa_mfma_bf16(const AttnParams& p, hipStream_t s);
@@ -110,5 +123,6 @@ hipError_t launch_score_simple(const ScoreParams& p, int dtype, hipStream_t s);
 hipError_t launch_select(const SelectParams& p, hipStream_t s);
 bool select_needs_pooled_buffer(const SelectParams& p);
 hipError_t launch_compact(const CompactParams& p, hipStream_t s);
+hipError_t launch_dense_full_mfma_bf16(const DenseFullParams& p, hipStream_t s);
 
 }  // namespace sdllm
