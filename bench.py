@@ -253,6 +253,27 @@ def main() -> int:
     }
     stage_gbs = {k: stage_bytes[k] / (stages[k + "_us"] * 1e-6) / 1e9 for k in stage_bytes}
 
+    # the row next to the hot path: full-sequence attention of cache states 0/1 (compute-bound)
+    dense_full = None
+    if w.dtype == "bf16" and w.head_dim == 128:
+        st0 = layers[0]
+        q_full = torch.randn(w.batch, w.n_q_heads, w.seq_len, w.head_dim, device=dev).to(w.torch_dtype)
+        out_full = torch.empty_like(q_full)
+        B.sdllm_dense_attn(shape, q_full, st0["k_full"], st0["v_full"], out_full)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(2):
+            B.sdllm_dense_attn(shape, q_full, st0["k_full"], st0["v_full"], out_full)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 2
+        flops = 4.0 * w.batch * w.n_q_heads * w.seq_len * w.seq_len * w.head_dim
+        dense_full = {"entry": "sdllm_dense_attn (one layer, all L query rows)", "ms": ms,
+                      "roofline": {"bound": "mfma", "achieved": flops / ms / 1e9, "peak": 2500.0, "unit": "TFLOP/s",
+                                   "frac": flops / ms / 1e9 / 2500.0}}
+        del q_full, out_full
+
     result = {
         "metric": "sparse block-step attention: block-steps/s per layer + achieved HBM GB/s (% of peak)",
         "value": calls / elapsed,
@@ -273,6 +294,7 @@ def main() -> int:
                      "kernel": "attn_mfma_bf16_kernel (sdllm_sparse_attn, cache_state 2)",
                      "algorithmic_bytes_per_launch": bytes_sparse, "avg_launch_us": sparse_launch_us},
         "stages_us_per_layer_call": stages,
+        "full_sequence_attention": dense_full,
         "stages_algorithmic_gbs": stage_gbs,
     }
     if inp0_host is not None:
