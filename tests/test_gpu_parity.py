@@ -280,3 +280,41 @@ def test_block_step_replays_identically_from_a_hip_graph():
         assert torch.equal(gl.out, eager_out), rep
         # eager work between replays
         gl.block_step(0, 1, q1, inp["k_full"], inp["v_full"])
+
+
+def test_very_long_segment_takes_the_streaming_select_variant():
+    # more than 36 864 candidates in one segment: the select kernel re-reads the pooled row instead
+    # of holding it in registers; the scoring runs on the MFMA path with a single head
+    _note("[case] 40k-candidate segment")
+    w = wl.WORKLOADS["dream_long"].scaled(n_q_heads=2, n_kv_heads=1, prompt=40000, gen=64, retention=0.3, sink=16)
+    inp = wl.make_block_inputs(w, n_steps=2, device=DEV)
+    shape = U.shape_for(w)
+    gl = U.GpuLayer(shape, DEV)
+    q = inp["q"][1].contiguous()
+    idx, pooled, score = gl.score_select(q, inp["k_full"])
+    idx_orc, pooled_orc, score_orc = U.oracle_score_select(shape, q, inp["k_full"])
+    np.testing.assert_allclose(score.cpu().double().numpy(), score_orc, rtol=3e-5, atol=1e-12)
+    ties = U.compare_index_rows(idx[0, 0], idx_orc[0, 0], pooled_orc[0, 0], w.seq_len, inp["block_off"], w.block,
+                                U.ranked_segments(shape))
+    _note(f"[done] ties in band: {ties}")
+    # same result without asking for the pooled row back
+    idx2, _, _ = gl.score_select(q, inp["k_full"], want_scores=False)
+    assert (idx2 == idx).all()
+
+
+def test_compaction_never_leaves_the_source_tensor():
+    # positions outside [0, L) in the index buffer are clamped, not followed
+    _note("[case] compact with out-of-range indices")
+    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=2, n_kv_heads=2, prompt=96, gen=64)
+    shape = U.shape_for(w)
+    gl = U.GpuLayer(shape, DEV)
+    k = torch.randn(w.batch, w.n_kv_heads, w.seq_len, w.head_dim, device=DEV).bfloat16()
+    v = torch.randn_like(k.float()).bfloat16()
+    idx = torch.randint(0, w.seq_len, (w.batch, w.n_kv_heads, gl.k_total), device=DEV, dtype=torch.int32)
+    idx[0, 0, 0] = -7
+    idx[0, 1, 3] = 2 ** 30
+    B.sdllm_compact_kv(shape, k, v, idx, gl.k_cache, gl.v_cache)
+    torch.cuda.synchronize()
+    clamped = idx.long().clamp(0, w.seq_len - 1)
+    want = torch.gather(k, 2, clamped[..., None].expand(-1, -1, -1, w.head_dim))
+    assert torch.equal(gl.k_cache[:, :, :gl.k_total], want)
