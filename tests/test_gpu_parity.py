@@ -318,3 +318,46 @@ def test_compaction_never_leaves_the_source_tensor():
     clamped = idx.long().clamp(0, w.seq_len - 1)
     want = torch.gather(k, 2, clamped[..., None].expand(-1, -1, -1, w.head_dim))
     assert torch.equal(gl.k_cache[:, :, :gl.k_total], want)
+
+
+def test_block_step_on_sequence_major_views():
+    # every tensor stored [B, rows, H, d] (the layout a fused QKV projection produces) and passed as
+    # [B, H, rows, d] views through the stride fields; GQA so that scoring, selection, compaction and
+    # both attention kernels all see non-trivial strides
+    _note("[case] block_step on [B, rows, H, d] storage")
+    w = wl.WORKLOADS["dream7b_gqa"].scaled(batch=2, prompt=500, gen=96)
+    inp = wl.make_block_inputs(w, n_steps=3, device=DEV)
+    o, b, d = inp["block_off"], w.block, w.head_dim
+
+    def seq_major(t):   # same values, [B, rows, H, d] storage
+        return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+
+    k_full, v_full = seq_major(inp["k_full"]), seq_major(inp["v_full"])
+    q = [seq_major(inp["q"][t]) for t in range(3)]
+    kb, vb = seq_major(inp["k_blk"][2]), seq_major(inp["v_blk"][2])
+    base = U.shape_for(w)
+    k_total, _, _ = B.sdllm_retained_count(base)
+    k_cache = torch.zeros(w.batch, k_total + 5, w.n_kv_heads, d, device=DEV, dtype=torch.bfloat16).permute(0, 2, 1, 3)
+    v_cache = torch.zeros_like(k_cache.permute(0, 2, 1, 3)).permute(0, 2, 1, 3)
+    out = torch.zeros(w.batch, b, w.n_q_heads, d, device=DEV, dtype=torch.bfloat16).permute(0, 2, 1, 3)
+    shape = B.make_shape(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=d, seq_len=w.seq_len,
+                         block_off=o, block_len=b, dtype=B.SDLLM_BF16, retention=w.retention, pool_kernel=w.pool_kernel,
+                         q_stride=B.strides_of(q[0]), kv_stride=B.strides_of(k_full), blk_stride=B.strides_of(kb),
+                         cache_stride=B.strides_of(k_cache), out_stride=B.strides_of(out))
+    idx = torch.zeros(w.batch, w.n_kv_heads, k_total, device=DEV, dtype=torch.int32)
+    ws = torch.empty(B.sdllm_workspace_bytes(shape, B.SDLLM_OP_BLOCK_STEP), dtype=torch.uint8, device=DEV)
+    assert B.sdllm_block_step(shape, 1, 1, q[1], k_full, v_full, idx, k_cache, v_cache, out, ws) == 1
+    torch.cuda.synchronize()
+    U.assert_close(out, U.oracle_attention_batch(q[1], k_full, v_full), "bf16", "dense, strided")
+    idx_orc, pooled_orc, _ = U.oracle_score_select(shape, q[1], k_full)
+    ig = idx.cpu().numpy().astype(np.int64)
+    for bi in range(w.batch):
+        for g in range(w.n_kv_heads):
+            U.compare_index_rows(ig[bi, g], idx_orc[bi, g], pooled_orc[bi, g], w.seq_len, o, b, U.ranked_segments(shape))
+    ex = idx.long()[..., None].expand(-1, -1, -1, d)
+    assert torch.equal(k_cache[:, :, :k_total], torch.gather(k_full, 2, ex))
+    assert torch.equal(v_cache[:, :, :k_total], torch.gather(v_full, 2, ex))
+    assert B.sdllm_block_step(shape, 2, 1, q[2], kb, vb, idx, k_cache, v_cache, out, ws) == 2
+    torch.cuda.synchronize()
+    ref = U.oracle_attention_batch(q[2], torch.cat([k_cache[:, :, :k_total], kb], 2), torch.cat([v_cache[:, :, :k_total], vb], 2))
+    U.assert_close(out, ref, "bf16", "sparse, strided")
