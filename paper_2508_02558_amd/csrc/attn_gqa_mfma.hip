@@ -3,7 +3,7 @@
 //
 // One workgroup serves one (batch, KV head) and a range of key tiles; wave w is query head
 // g*G + w.  The K/V tiles are loaded ONCE per workgroup, cooperatively and fully coalesced, into a
-// double-buffered LDS stage of one 32-key tile (K and V: 17 KB), and all G waves run their own
+// double-buffered LDS stage of one 32-key tile (K and V: 18.5 KB), and all G waves run their own
 // logits / online softmax / PV product against the same stage, so K and V leave HBM (and L2) once
 // however many query heads read them.  One workgroup barrier per tile; the next tile's global
 // loads are in flight while the current one is computed.  Each wave owns its head's result, so there
@@ -12,7 +12,7 @@
 
 namespace sdllm {
 
-constexpr int kStageBytes = 2 * kTileBytes;   // one 32-key tile: K, V
+constexpr int kStageBytes = kTileBytes + kVTileBytes;   // one 32-key tile: K, V
 constexpr int kTileChunks = 512;              // 16-byte pieces of one tensor of a tile
 constexpr int kMaxStageIters = 4;             // pieces per thread and tensor with the fewest threads (G = 2)
 
@@ -41,9 +41,8 @@ __device__ __forceinline__ void store_stage(uint8_t* stage, int tid, int nthread
   for (int j = 0; j < kMaxStageIters; ++j) {
     const int c = tid + j * nthreads;
     if (c < kTileChunks) {
-      const uint32_t off = tile_off(c >> 4, c & 15);
-      *reinterpret_cast<u32x4*>(stage + off) = kreg[j];
-      *reinterpret_cast<u32x4*>(stage + kTileBytes + off) = vreg[j];
+      *reinterpret_cast<u32x4*>(stage + tile_off(c >> 4, c & 15)) = kreg[j];
+      *reinterpret_cast<u32x4*>(stage + kTileBytes + vtile_off(c >> 4, c & 15)) = vreg[j];
     }
   }
 }
@@ -97,7 +96,7 @@ __global__ __launch_bounds__(512) void attn_gqa_mfma_bf16_kernel(const AttnParam
     f32x16 sc;
     const float m_loc = tile_logits(stage, qf, rows, p.scale_log2, half, col, sc);
     tile_softmax(sc, m_loc, p.scale_log2, m_run, l_run, acc);
-    tile_pv(stage + kTileBytes, sc, half, col, acc);
+    tile_pv(stage + kTileBytes, sc, lane, acc);
     if (more) {
       store_stage(smem + ((t + 1 - t_begin) & 1) * kStageBytes, tid, nthreads, kreg, vreg);
       rows = ts.rows;

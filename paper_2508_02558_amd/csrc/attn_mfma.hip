@@ -20,7 +20,7 @@
 
 namespace sdllm {
 
-constexpr int kWaveLds = 2 * kTileBytes + 512;    // K tile, V tile (later: 64 lanes x 272 B of accumulators), (max, sum)
+constexpr int kWaveLds = kTileBytes + kVTileBytes + 512;    // K tile, V tile (later: 64 lanes x 272 B of accumulators), (max, sum)
 
 size_t attn_mfma_lds_bytes(int waves) { return (size_t)waves * kWaveLds; }
 
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     const int tn = t + nw;
     store_rows(lds_k, lane, reg);
     if (DEEP) {
-      store_rows(lds_v, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
+      store_rows_v(lds_v, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
       wave_lds_sync();
       if (tn < t_end) {                              // both tensors of tile t+1 fly during tile t
         ts = tile_src(sp, tn, stride);
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     tile_softmax(s, m_loc, p.scale_log2, m_run, l_run, acc);
 
     if (!DEEP) {
-      store_rows(lds_v, lane, reg);
+      store_rows_v(lds_v, lane, reg);
       wave_lds_sync();
       if (tn < t_end) {                              // K(t+1) flies during the PV product
         ts = tile_src(sp, tn, stride);
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
       }
     }
 
-    tile_pv(lds_v, s, half, col, acc);
+    tile_pv(lds_v, s, lane, acc);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }
@@ -165,16 +165,18 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   }
 
   // Merge the waves of the workgroup, all waves working: every wave parks its 64 accumulator
-  // registers per lane in its own LDS region ([lane][i][e], lane stride 272 B) together with its
-  // row (max, sum); after one barrier wave w reduces register slots i = w, w+nw, ... over all waves.
+  // registers per lane in its own LDS region ([lane][e][i], lane stride 272 B) together with its
+  // row (max, sum); after one barrier wave w reduces the 4-register slots w, w+nw, ... (of 16) over all waves.
   // All LDS reads of a slot are issued before any is used, so the merge costs a few hundred cycles.
   {
     uint8_t* mine = smem + wave * kWaveLds;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const f32x4 v = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-      *reinterpret_cast<f32x4*>(mine + lane * kRowBytes + i * 16) = v;
-    }
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 v = {acc[e][i4 * 4], acc[e][i4 * 4 + 1], acc[e][i4 * 4 + 2], acc[e][i4 * 4 + 3]};
+        *reinterpret_cast<f32x4*>(mine + lane * kRowBytes + (e * 4 + i4) * 16) = v;
+      }
     float* my_ml = reinterpret_cast<float*>(mine + 64 * kRowBytes);
     if (lane < 32) {
       my_ml[lane] = m_run; my_ml[32 + lane] = l_tot;
@@ -222,15 +224,15 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     f32x4 o4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int w = 0; w < kMaxWavesPerWg; ++w) o4 += part[w] * f_w[w];
-    const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
+    const int d0 = out_col0(i >> 2, i & 3, half);   // slot i = (e, i4): four consecutive output columns
     if (p.n_split == 1) {
       bf16x4 ob;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o4[e] * inv);
+      for (int r = 0; r < 4; ++r) ob[r] = (__bf16)(o4[r] * inv);
       char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
-      *reinterpret_cast<bf16x4*>(op + mrow * 8) = ob;
+      *reinterpret_cast<bf16x4*>(op + d0 * 2) = ob;
     } else {
-      *reinterpret_cast<f32x4*>(p.part_o + (slot * 32 + col) * 128 + mrow * 4) = o4;
+      *reinterpret_cast<f32x4*>(p.part_o + (slot * 32 + col) * 128 + d0) = o4;
     }
   }
   if (p.n_split > 1 && wave == 0 && lane < 32) {

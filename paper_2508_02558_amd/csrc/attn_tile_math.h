@@ -6,8 +6,8 @@
 //   8*(i/4) + 4*half + i%4 of the tile for query row `col`, so softmax row reductions are in-lane
 //   plus one exchange between the two halves.
 //   O^T += V_tile^T P^T: P^T (registers 8*step .. 8*step+7 of the logits, as bf16) is the B operand;
-//   V is read from LDS as 8-byte pieces of four head-dim columns and regrouped with v_perm so that
-//   MFMA e (0..3) produces columns 4m+e, m = 8*(i/4) + 4*half + i%4.
+//   V^T fragments come from the row-major V tile through the transposing LDS read; MFMA e (0..3)
+//   produces columns 32e + m, m = 8*(i/4) + 4*half + i%4.
 #pragma once
 
 #include "mfma_tile.h"
@@ -77,31 +77,37 @@ __device__ __forceinline__ void tile_softmax(f32x16& s, float m_loc, float scale
   l_run += l_loc;
 }
 
-// O^T[col 4m+e, query] += V_tile^T P^T, 16 keys per MFMA step.
-__device__ __forceinline__ void tile_pv(const uint8_t* lds_v, const f32x16& s, int half, int col, f32x16 (&acc)[4]) {
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef short i16x8 __attribute__((ext_vector_type(8)));
+
+// O^T[column 32e + m, query] += V_tile^T P^T, 16 keys per MFMA step.  The A operand (V^T: 8 keys of
+// one head-dim column per lane) comes straight out of the row-major V tile through gfx950's
+// transposing LDS read (ds_read_b64_tr_b16): within each group of 16 lanes, lane i receives element
+// i%4 of the 8-byte pieces addressed by lanes i/4, i/4+4, i/4+8, i/4+12.  Pointing lane s of a group
+// at key row (s/4) and column piece (s%4) therefore hands lane i four consecutive keys of column
+// (16 * group parity + i); two such reads make one operand, no register shuffling.
+__device__ __forceinline__ void tile_pv(const uint8_t* lds_v, const f32x16& s, int lane, f32x16 (&acc)[4]) {
+  const int half = lane >> 5, grp = (lane >> 4) & 1, s16 = lane & 15;
+  const uint8_t* base = lds_v + (half * 4 + (s16 >> 2)) * kVRowBytes + (grp * 16 + (s16 & 3) * 4) * 2;
 #pragma unroll
   for (int step = 0; step < 2; ++step) {
     bf16x8 pb;
 #pragma unroll
     for (int j = 0; j < 8; ++j) pb[j] = (__bf16)s[step * 8 + j];
-    u32x2 vv[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int key_local = step * 16 + (j >> 2) * 8 + half * 4 + (j & 3);
-      vv[j] = *reinterpret_cast<const u32x2*>(lds_v + tile_off(key_local, col >> 1) + ((col & 1) << 3));
-    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      u32x4 w;
-      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-      w.x = __builtin_amdgcn_perm(e < 2 ? vv[1].x : vv[1].y, e < 2 ? vv[0].x : vv[0].y, sel);
-      w.y = __builtin_amdgcn_perm(e < 2 ? vv[3].x : vv[3].y, e < 2 ? vv[2].x : vv[2].y, sel);
-      w.z = __builtin_amdgcn_perm(e < 2 ? vv[5].x : vv[5].y, e < 2 ? vv[4].x : vv[4].y, sel);
-      w.w = __builtin_amdgcn_perm(e < 2 ? vv[7].x : vv[7].y, e < 2 ? vv[6].x : vv[6].y, sel);
-      acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pb, acc[e], 0, 0, 0);
+      typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+      const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(base + (step * 16) * kVRowBytes + e * 64));
+      const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(base + (step * 16 + 8) * kVRowBytes + e * 64));
+      const i16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, acc[e], 0, 0, 0);
     }
   }
 }
+
+// Register (e, i) of a lane is output column 32e + 8*(i/4) + 4*half + i%4 of query row lane%32: four
+// consecutive registers are four consecutive columns.
+__device__ __forceinline__ int out_col0(int e, int i4, int half) { return 32 * e + 8 * i4 + 4 * half; }
 
 // One wave owns the complete result of a head (or of a key split of it): normalised bf16 rows to
 // `out_row` (n_split == 1) or fp32 numerators + (max, sum) to the split-KV partial buffers.
@@ -111,22 +117,22 @@ __device__ __forceinline__ void write_wave_result(const f32x16 (&acc)[4], float 
   if (final_out) {
     const float inv = 1.f / l_tot;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
-      bf16x4 o4;
-      o4[0] = (__bf16)(acc[0][i] * inv);
-      o4[1] = (__bf16)(acc[1][i] * inv);
-      o4[2] = (__bf16)(acc[2][i] * inv);
-      o4[3] = (__bf16)(acc[3][i] * inv);
-      *reinterpret_cast<bf16x4*>(out_row + mrow * 8) = o4;
-    }
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        bf16x4 o4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o4[r] = (__bf16)(acc[e][i4 * 4 + r] * inv);
+        *reinterpret_cast<bf16x4*>(out_row + out_col0(e, i4, half) * 2) = o4;
+      }
   } else {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
-      const f32x4 o4 = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-      *reinterpret_cast<f32x4*>(part_o_row + mrow * 4) = o4;
-    }
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 o4 = {acc[e][i4 * 4], acc[e][i4 * 4 + 1], acc[e][i4 * 4 + 2], acc[e][i4 * 4 + 3]};
+        *reinterpret_cast<f32x4*>(part_o_row + out_col0(e, i4, half)) = o4;
+      }
     if (lane < 32) {
       part_ml_slot[lane] = m_run;
       part_ml_slot[32 + lane] = l_tot;

@@ -18,7 +18,8 @@ namespace sdllm {
 constexpr int kFullWaves = 8;
 constexpr int kFullRowsPerWg = kFullWaves * 32;
 constexpr int kFullStageTiles = 2;
-constexpr int kFullStageBytes = kFullStageTiles * 2 * kTileBytes;   // (K, V) x tiles
+constexpr int kFullKvTileBytes = kTileBytes + kVTileBytes;             // K tile + V tile
+constexpr int kFullStageBytes = kFullStageTiles * kFullKvTileBytes;
 
 size_t dense_full_lds_bytes() { return 2 * (size_t)kFullStageBytes; }
 
@@ -39,11 +40,10 @@ __device__ __forceinline__ void full_load_stage(const char* k_base, const char* 
 
 __device__ __forceinline__ void full_store_stage(uint8_t* stage, int tid, const u32x4 (&kreg)[kFullStageTiles],
                                                  const u32x4 (&vreg)[kFullStageTiles]) {
-  const uint32_t off = tile_off(tid >> 4, tid & 15);
 #pragma unroll
   for (int j = 0; j < kFullStageTiles; ++j) {
-    *reinterpret_cast<u32x4*>(stage + (2 * j) * kTileBytes + off) = kreg[j];
-    *reinterpret_cast<u32x4*>(stage + (2 * j + 1) * kTileBytes + off) = vreg[j];
+    *reinterpret_cast<u32x4*>(stage + j * kFullKvTileBytes + tile_off(tid >> 4, tid & 15)) = kreg[j];
+    *reinterpret_cast<u32x4*>(stage + j * kFullKvTileBytes + kTileBytes + vtile_off(tid >> 4, tid & 15)) = vreg[j];
   }
 }
 
@@ -102,9 +102,9 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
         const int rows = min(kTileKeys, n_keys - (s * stage_keys + j * kTileKeys));
         if (rows > 0) {
           f32x16 sc;
-          const float m_loc = tile_logits(stage + (2 * j) * kTileBytes, qf, rows, p.scale_log2, half, col, sc);
+          const float m_loc = tile_logits(stage + j * kFullKvTileBytes, qf, rows, p.scale_log2, half, col, sc);
           tile_softmax(sc, m_loc, p.scale_log2, m_run, l_run, acc);
-          tile_pv(stage + (2 * j + 1) * kTileBytes, sc, half, col, acc);
+          tile_pv(stage + j * kFullKvTileBytes + kTileBytes, sc, lane, acc);
         }
       }
     }
@@ -115,18 +115,8 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
   if (!wave_valid) return;
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   if (row_valid) {
-    const float inv = 1.f / l_tot;
     char* out_row = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + (int64_t)q_row * p.o_sr);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int mrow = (i >> 2) * 8 + half * 4 + (i & 3);
-      bf16x4 o4;
-      o4[0] = (__bf16)(acc[0][i] * inv);
-      o4[1] = (__bf16)(acc[1][i] * inv);
-      o4[2] = (__bf16)(acc[2][i] * inv);
-      o4[3] = (__bf16)(acc[3][i] * inv);
-      *reinterpret_cast<bf16x4*>(out_row + mrow * 8) = o4;
-    }
+    write_wave_result(acc, m_run, l_tot, lane, half, col, true, out_row, nullptr, nullptr);
   }
 }
 

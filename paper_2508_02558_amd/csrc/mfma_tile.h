@@ -17,6 +17,13 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int kRowBytes = 256 + 16;               // 128 bf16 + one 16-byte pad: rows rotate over the banks
 constexpr int kTileBytes = kTileKeys * kRowBytes; // one 32 x 128 bf16 tile in LDS
 
+// V tiles use 320-byte rows: the transposing LDS read of the PV product touches four consecutive
+// rows x 64 bytes per 32 lanes, and a row offset of 64 bytes (mod 256) puts those on 64 distinct banks.
+constexpr int kVRowBytes = 256 + 64;
+constexpr int kVTileBytes = kTileKeys * kVRowBytes;
+
+__device__ __forceinline__ uint32_t vtile_off(int row, int chunk) { return (uint32_t)(row * kVRowBytes + (chunk << 4)); }
+
 __device__ __forceinline__ uint32_t tile_off(int row, int chunk) {
   // padded rows: the sixteen lanes that read one chunk column of sixteen rows hit sixteen different
   // 16-byte bank groups, and every address is a per-lane base plus a compile-time constant
@@ -44,6 +51,12 @@ __device__ __forceinline__ void store_rows(uint8_t* lds_tile, int lane, const u3
 #pragma unroll
   for (int j = 0; j < 8; ++j)
     *reinterpret_cast<u32x4*>(lds_tile + tile_off(j * 4 + (lane >> 4), lane & 15)) = reg[j];
+}
+
+__device__ __forceinline__ void store_rows_v(uint8_t* lds_tile, int lane, const u32x4 (&reg)[8]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    *reinterpret_cast<u32x4*>(lds_tile + vtile_off(j * 4 + (lane >> 4), lane & 15)) = reg[j];
 }
 
 // make this wave's LDS writes visible to its own later reads (wave-private tiles need no s_barrier)
