@@ -1,13 +1,13 @@
 // Gather-compaction of the retained K/V rows into the dense sparse cache (Sec. 3.3 fourth
-// equation; Alg. 1 steps 12-14).  Pure byte movement: each thread copies one 16-byte chunk of four
+// equation; Alg. 1 steps 12-14).  Pure byte movement: each thread copies one 16-byte chunk of two
 // consecutive cache rows of K and of V, so a wavefront reads and writes whole rows with 16-byte
-// accesses and has 8 loads in flight per lane.
+// non-temporal accesses and has 4 loads in flight per lane (more in flight measured slower).
 #include "sdllm_internal.h"
 
 namespace sdllm {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-constexpr int kRowsPerThread = 4;
+constexpr int kRowsPerThread = 2;
 
 __global__ __launch_bounds__(256) void compact_kernel(const CompactParams p) {
   const int chunks = p.row_bytes >> 4;
