@@ -30,11 +30,14 @@ __device__ __forceinline__ float tile_logits(const uint8_t* lds_k, const bf16x8 
                                              int half, int col, f32x16& s) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) s[i] = 0.f;
+  // all eight K fragments are requested before the first MFMA (the scheduling barrier keeps the
+  // compiler from sinking each read next to its use, which would expose the LDS latency eight times)
+  bf16x8 a[8];
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(lds_k + tile_off(col, kk * 2 + half));
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s, 0, 0, 0);
-  }
+  for (int kk = 0; kk < 8; ++kk) a[kk] = *reinterpret_cast<const bf16x8*>(lds_k + tile_off(col, kk * 2 + half));
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], qf[kk], s, 0, 0, 0);
   if (rows < kTileKeys) {   // only the last tile of a segment is ragged (wave-uniform)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -86,23 +89,54 @@ typedef short i16x8 __attribute__((ext_vector_type(8)));
 // i%4 of the 8-byte pieces addressed by lanes i/4, i/4+4, i/4+8, i/4+12.  Pointing lane s of a group
 // at key row (s/4) and column piece (s%4) therefore hands lane i four consecutive keys of column
 // (16 * group parity + i); two such reads make one operand, no register shuffling.
-__device__ __forceinline__ void tile_pv(const uint8_t* lds_v, const f32x16& s, int lane, f32x16 (&acc)[4]) {
+struct PvFrags { i16x8 av[2][4]; };
+
+// The sixteen transposed reads of one V tile (all requested together; see tile_logits).
+__device__ __forceinline__ void tile_pv_load(const uint8_t* lds_v, int lane, PvFrags& f) {
+  typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
   const int half = lane >> 5, grp = (lane >> 4) & 1, s16 = lane & 15;
   const uint8_t* base = lds_v + (half * 4 + (s16 >> 2)) * kVRowBytes + (grp * 16 + (s16 & 3) * 4) * 2;
 #pragma unroll
-  for (int step = 0; step < 2; ++step) {
-    bf16x8 pb;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) pb[j] = (__bf16)s[step * 8 + j];
+  for (int step = 0; step < 2; ++step)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
       const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(base + (step * 16) * kVRowBytes + e * 64));
       const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(base + (step * 16 + 8) * kVRowBytes + e * 64));
-      const i16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, acc[e], 0, 0, 0);
+      f.av[step][e] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
-  }
+}
+
+__device__ __forceinline__ void tile_pv_mma(const PvFrags& f, const f32x16& s, f32x16 (&acc)[4]) {
+  bf16x8 pb[2];
+#pragma unroll
+  for (int step = 0; step < 2; ++step)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pb[step][j] = (__bf16)s[step * 8 + j];
+#pragma unroll
+  for (int step = 0; step < 2; ++step)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      acc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[step][e]), pb[step], acc[e], 0, 0, 0);
+}
+
+__device__ __forceinline__ void tile_pv(const uint8_t* lds_v, const f32x16& s, int lane, f32x16 (&acc)[4]) {
+  PvFrags f;
+  tile_pv_load(lds_v, lane, f);
+  __builtin_amdgcn_sched_barrier(0);
+  tile_pv_mma(f, s, acc);
+}
+
+// One whole tile when K and V are both already in LDS (shared-stage kernels): the V fragments are
+// requested right after the logits MFMAs are issued, so their LDS latency hides under the softmax.
+__device__ __forceinline__ void tile_full(const uint8_t* lds_k, const uint8_t* lds_v, const bf16x8 (&qf)[8], int rows,
+                                          float scale_log2, int lane, float& m_ref, float& l_run, f32x16 (&acc)[4]) {
+  f32x16 s;
+  const float m_loc = tile_logits(lds_k, qf, rows, scale_log2, lane >> 5, lane & 31, s);
+  PvFrags f;
+  tile_pv_load(lds_v, lane, f);
+  __builtin_amdgcn_sched_barrier(0);
+  tile_softmax(s, m_loc, scale_log2, m_ref, l_run, acc);
+  tile_pv_mma(f, s, acc);
 }
 
 // Register (e, i) of a lane is output column 32e + 8*(i/4) + 4*half + i%4 of query row lane%32: four

@@ -101,10 +101,8 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
       for (int j = 0; j < kFullStageTiles; ++j) {
         const int rows = min(kTileKeys, n_keys - (s * stage_keys + j * kTileKeys));
         if (rows > 0) {
-          f32x16 sc;
-          const float m_loc = tile_logits(stage + j * kFullKvTileBytes, qf, rows, p.scale_log2, half, col, sc);
-          tile_softmax(sc, m_loc, p.scale_log2, m_run, l_run, acc);
-          tile_pv(stage + j * kFullKvTileBytes + kTileBytes, sc, lane, acc);
+          tile_full(stage + j * kFullKvTileBytes, stage + j * kFullKvTileBytes + kTileBytes, qf, rows, p.scale_log2, lane,
+                    m_run, l_run, acc);
         }
       }
     }
