@@ -24,20 +24,23 @@ __device__ __forceinline__ void load_q_frags(const char* q_row, int half, bf16x8
   }
 }
 
-// Raw logits of one tile (unscaled; keys >= rows become -inf).  Returns the row max over the tile
-// in the scaled log2 domain (scale_log2 > 0), already exchanged between the halves.
-__device__ __forceinline__ float tile_logits(const uint8_t* lds_k, const bf16x8 (&qf)[8], int rows, float scale_log2,
-                                             int half, int col, f32x16& s) {
-#pragma unroll
-  for (int i = 0; i < 16; ++i) s[i] = 0.f;
-  // all eight K fragments are requested before the first MFMA (the scheduling barrier keeps the
-  // compiler from sinking each read next to its use, which would expose the LDS latency eight times)
-  bf16x8 a[8];
+// The eight K fragments (A operands) of one tile, all requested together.
+__device__ __forceinline__ void tile_k_load(const uint8_t* lds_k, int half, int col, bf16x8 (&a)[8]) {
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) a[kk] = *reinterpret_cast<const bf16x8*>(lds_k + tile_off(col, kk * 2 + half));
-  __builtin_amdgcn_sched_barrier(0);
+}
+
+// logits^T = K_tile Q^T from fragments already in registers: raw, unscaled.
+__device__ __forceinline__ void tile_logits_mma(const bf16x8 (&a)[8], const bf16x8 (&qf)[8], f32x16& s) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], qf[kk], s, 0, 0, 0);
+}
+
+// Keys >= rows become -inf; returns the row max over the tile in the scaled log2 domain
+// (scale_log2 > 0), already exchanged between the halves.
+__device__ __forceinline__ float tile_mask_max(f32x16& s, int rows, float scale_log2, int half) {
   if (rows < kTileKeys) {   // only the last tile of a segment is ragged (wave-uniform)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -50,6 +53,19 @@ __device__ __forceinline__ float tile_logits(const uint8_t* lds_k, const bf16x8 
   for (int i = 1; i < 16; ++i) m_loc = fmaxf(m_loc, s[i]);
   m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
   return m_loc * scale_log2;
+}
+
+// Raw logits of one tile (unscaled; keys >= rows become -inf).  Returns the row max over the tile
+// in the scaled log2 domain.  All eight K fragments are requested before the first MFMA (the
+// scheduling barrier keeps the compiler from sinking each read next to its use, which would expose
+// the LDS latency eight times).
+__device__ __forceinline__ float tile_logits(const uint8_t* lds_k, const bf16x8 (&qf)[8], int rows, float scale_log2,
+                                             int half, int col, f32x16& s) {
+  bf16x8 a[8];
+  tile_k_load(lds_k, half, col, a);
+  __builtin_amdgcn_sched_barrier(0);
+  tile_logits_mma(a, qf, s);
+  return tile_mask_max(s, rows, scale_log2, half);
 }
 
 // Softmax numerators of one tile against a per-row reference m_ref that only moves when some row's
@@ -126,17 +142,32 @@ __device__ __forceinline__ void tile_pv(const uint8_t* lds_v, const f32x16& s, i
   tile_pv_mma(f, s, acc);
 }
 
-// One whole tile when K and V are both already in LDS (shared-stage kernels): the V fragments are
-// requested right after the logits MFMAs are issued, so their LDS latency hides under the softmax.
-__device__ __forceinline__ void tile_full(const uint8_t* lds_k, const uint8_t* lds_v, const bf16x8 (&qf)[8], int rows,
-                                          float scale_log2, int lane, float& m_ref, float& l_run, f32x16 (&acc)[4]) {
-  f32x16 s;
-  const float m_loc = tile_logits(lds_k, qf, rows, scale_log2, lane >> 5, lane & 31, s);
-  PvFrags f;
-  tile_pv_load(lds_v, lane, f);
-  __builtin_amdgcn_sched_barrier(0);
-  tile_softmax(s, m_loc, scale_log2, m_ref, l_run, acc);
-  tile_pv_mma(f, s, acc);
+// NT whole tiles whose K and V are already in LDS (shared-stage kernels), software-pipelined over the
+// LDS latency: the V fragments of a tile are requested right after its logits MFMAs are issued (they
+// arrive under the softmax), and the K fragments of the NEXT tile right before this tile's PV MFMAs
+// are issued (they arrive under the PV product).  tile j: K at base + j*tile_stride, V kTileBytes on.
+template <int NT>
+__device__ __forceinline__ void tiles_pipelined(const uint8_t* base, int tile_stride, const bf16x8 (&qf)[8], int rows_left,
+                                                float scale_log2, int lane, float& m_ref, float& l_run, f32x16 (&acc)[4]) {
+  const int half = lane >> 5, col = lane & 31;
+  bf16x8 a[8];
+  tile_k_load(base, half, col, a);
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int rows = min(kTileKeys, rows_left - j * kTileKeys);
+    if (rows <= 0) break;
+    __builtin_amdgcn_sched_barrier(0);
+    f32x16 s;
+    tile_logits_mma(a, qf, s);
+    PvFrags f;
+    tile_pv_load(base + j * tile_stride + kTileBytes, lane, f);
+    __builtin_amdgcn_sched_barrier(0);
+    const float m_loc = tile_mask_max(s, rows, scale_log2, half);
+    tile_softmax(s, m_loc, scale_log2, m_ref, l_run, acc);
+    if (j + 1 < NT && rows_left - (j + 1) * kTileKeys > 0) tile_k_load(base + (j + 1) * tile_stride, half, col, a);
+    __builtin_amdgcn_sched_barrier(0);
+    tile_pv_mma(f, s, acc);
+  }
 }
 
 // Register (e, i) of a lane is output column 32e + 8*(i/4) + 4*half + i%4 of query row lane%32: four

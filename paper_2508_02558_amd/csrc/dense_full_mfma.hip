@@ -96,16 +96,9 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
   for (int s = 0; s < nstages; ++s) {
     if (s + 1 < nstages) full_load_stage(k_base, v_base, stride, (s + 1) * stage_keys, n_keys, tid, kreg, vreg);
     const uint8_t* stage = smem + (s & 1) * kFullStageBytes;
-    if (wave_valid) {
-#pragma unroll
-      for (int j = 0; j < kFullStageTiles; ++j) {
-        const int rows = min(kTileKeys, n_keys - (s * stage_keys + j * kTileKeys));
-        if (rows > 0) {
-          tile_full(stage + j * kFullKvTileBytes, stage + j * kFullKvTileBytes + kTileBytes, qf, rows, p.scale_log2, lane,
-                    m_run, l_run, acc);
-        }
-      }
-    }
+    if (wave_valid)
+      tiles_pipelined<kFullStageTiles>(stage, kFullKvTileBytes, qf, n_keys - s * stage_keys, p.scale_log2, lane, m_run,
+                                       l_run, acc);
     if (s + 1 < nstages) full_store_stage(smem + ((s + 1) & 1) * kFullStageBytes, tid, kreg, vreg);
     __syncthreads();
   }
