@@ -261,6 +261,25 @@ def main() -> int:
     }
     stage_gbs = {k: stage_bytes[k] / (stages[k + "_us"] * 1e-6) / 1e9 for k in stage_bytes}
 
+    # what the memory system delivers for the attention kernel's access pattern: a bare streaming
+    # read of the sparse step's byte count, rotated over distinct buffers like the layers are
+    n_probe = 8
+    probe_bufs = [torch.empty(bytes_sparse // 16 * 16, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(n_probe)]
+    probe_sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    for pb in probe_bufs:
+        B.sdllm_stream_read_probe(pb, probe_sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(4):
+        for pb in probe_bufs:
+            B.sdllm_stream_read_probe(pb, probe_sink)
+    e1.record()
+    torch.cuda.synchronize()
+    probe_us = 1e3 * e0.elapsed_time(e1) / (4 * n_probe)
+    read_ceiling_gbs = probe_bufs[0].numel() / (probe_us * 1e-6) / 1e9
+    del probe_bufs
+
     # the row next to the hot path: full-sequence attention of cache states 0/1 (compute-bound)
     dense_full = None
     if w.dtype == "bf16" and w.head_dim == 128:
@@ -300,7 +319,9 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "kernel": "attn_mfma_bf16_kernel (sdllm_sparse_attn, cache_state 2)",
-                     "algorithmic_bytes_per_launch": bytes_sparse, "avg_launch_us": sparse_launch_us},
+                     "algorithmic_bytes_per_launch": bytes_sparse, "avg_launch_us": sparse_launch_us,
+                     "streaming_read_ceiling": {"us_for_same_bytes": probe_us, "GB/s": read_ceiling_gbs,
+                                                "achieved_over_ceiling": achieved / read_ceiling_gbs}},
         "stages_us_per_layer_call": stages,
         "full_sequence_attention": dense_full,
         "stages_algorithmic_gbs": stage_gbs,

@@ -28,7 +28,7 @@ SDLLM_OP_SCORE_SELECT, SDLLM_OP_COMPACT_KV, SDLLM_OP_SPARSE_ATTN, SDLLM_OP_BLOCK
 
 EXPORTED = ("sdllm_error_string", "sdllm_version", "sdllm_retained_count", "sdllm_workspace_bytes",
             "sdllm_cache_state", "sdllm_score_select", "sdllm_compact_kv", "sdllm_sparse_attn",
-            "sdllm_block_step", "sdllm_dense_attn")
+            "sdllm_block_step", "sdllm_dense_attn", "sdllm_stream_read_probe")
 
 
 class sdllm_shape_t(ctypes.Structure):
@@ -85,6 +85,8 @@ def load() -> ctypes.CDLL:
     lib.sdllm_block_step.argtypes = [shp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, i32p]
     lib.sdllm_dense_attn.restype = i32
     lib.sdllm_dense_attn.argtypes = [shp, vp, ctypes.POINTER(ctypes.c_int64), vp, vp, vp, ctypes.POINTER(ctypes.c_int64), vp]
+    lib.sdllm_stream_read_probe.restype = i32
+    lib.sdllm_stream_read_probe.argtypes = [vp, sz, vp, vp]
     _lib = lib
     return lib
 
@@ -205,3 +207,8 @@ def sdllm_dense_attn(shape, q_full, k_full, v_full, out_full, stream=None) -> No
     os_ = (ctypes.c_int64 * 3)(*strides_of(out_full))
     _check(load().sdllm_dense_attn(ctypes.byref(shape), _ptr(q_full), qs, _ptr(k_full), _ptr(v_full), _ptr(out_full), os_,
                                    _stream(stream)), "sdllm_dense_attn")
+
+
+def sdllm_stream_read_probe(src, sink=None, stream=None) -> None:
+    _check(load().sdllm_stream_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)),
+           "sdllm_stream_read_probe")

@@ -494,4 +494,9 @@ int32_t sdllm_dense_attn(const sdllm_shape_t* shape, const void* q_full, const i
   return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
 }
 
+int32_t sdllm_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !aligned16(src)) return SDLLM_ERR_INVALID_ARG;
+  return launch_stream_read(src, bytes, (uint32_t*)sink, (hipStream_t)stream) == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
+}
+
 }  // extern "C"

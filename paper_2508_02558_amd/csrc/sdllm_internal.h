@@ -124,5 +124,6 @@ hipError_t launch_select(const SelectParams& p, hipStream_t s);
 bool select_needs_pooled_buffer(const SelectParams& p);
 hipError_t launch_compact(const CompactParams& p, hipStream_t s);
 hipError_t launch_dense_full_mfma_bf16(const DenseFullParams& p, hipStream_t s);
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
 
 }  // namespace sdllm
