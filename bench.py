@@ -322,6 +322,14 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": bytes_sparse, "avg_launch_us": sparse_launch_us,
                      "streaming_read_ceiling": {"us_for_same_bytes": probe_us, "GB/s": read_ceiling_gbs,
                                                 "achieved_over_ceiling": achieved / read_ceiling_gbs}},
+        # the comparator the workload names: a dense full-cache scheme pays the dense block-row attention
+        # at every one of the T denoising steps of a block (same kernel over all L keys)
+        "vs_dense_full_cache": {
+            "sparse_path_us_per_block_per_layer": 1e6 * elapsed / (args.steps * n_layers),
+            "dense_cache_us_per_block_per_layer": T * stages["dense_block_attn_us"],
+            "attention_path_speedup": T * stages["dense_block_attn_us"] / (1e6 * elapsed / (args.steps * n_layers)),
+            "us_per_generated_token_sparse": 1e6 * elapsed / (args.steps * w.batch * b),
+            "us_per_generated_token_dense_cache": T * stages["dense_block_attn_us"] * n_layers / (w.batch * b)},
         "stages_us_per_layer_call": stages,
         "full_sequence_attention": dense_full,
         "stages_algorithmic_gbs": stage_gbs,
