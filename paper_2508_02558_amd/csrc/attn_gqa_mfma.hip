@@ -113,13 +113,9 @@ __global__ __launch_bounds__(512) void attn_gqa_mfma_bf16_kernel(const AttnParam
 
 template <int NSEG>
 static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_gqa_mfma_bf16_kernel<NSEG>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_gqa_lds_bytes());
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOptIn lds;
+  const hipError_t e = lds.ensure(reinterpret_cast<const void*>(attn_gqa_mfma_bf16_kernel<NSEG>), (int)attn_gqa_lds_bytes());
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_gqa_mfma_bf16_kernel<NSEG>, dim3(p.n_split, p.batch * p.hkv), dim3(p.group * kWave),
                      attn_gqa_lds_bytes(), s, p);
   return hipGetLastError();

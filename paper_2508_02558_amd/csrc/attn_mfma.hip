@@ -244,13 +244,10 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
 template <int NSEG, bool STATS, bool DEEP, bool SHARED_KV>
 static hipError_t launch_variant(const AttnParams& p, hipStream_t s) {
   const int nwg = p.batch * p.hq * p.n_split;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_bf16_kernel<NSEG, STATS, DEEP, SHARED_KV>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(kMaxWavesPerWg));
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOptIn lds;
+  const hipError_t e = lds.ensure(reinterpret_cast<const void*>(attn_mfma_bf16_kernel<NSEG, STATS, DEEP, SHARED_KV>),
+                                  (int)attn_mfma_lds_bytes(kMaxWavesPerWg));
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_mfma_bf16_kernel<NSEG, STATS, DEEP, SHARED_KV>), dim3(nwg), dim3(p.waves * kWave),
                      attn_mfma_lds_bytes(p.waves), s, p);
   return hipGetLastError();

@@ -112,13 +112,9 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
 }
 
 hipError_t launch_dense_full_mfma_bf16(const DenseFullParams& p, hipStream_t s) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dense_full_mfma_bf16_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)dense_full_lds_bytes());
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOptIn lds;
+  const hipError_t e = lds.ensure(reinterpret_cast<const void*>(dense_full_mfma_bf16_kernel), (int)dense_full_lds_bytes());
+  if (e != hipSuccess) return e;
   const int qblocks = (p.seq_len + kFullRowsPerWg - 1) / kFullRowsPerWg;
   hipLaunchKernelGGL(dense_full_mfma_bf16_kernel, dim3(qblocks * p.batch * p.hq), dim3(512), dense_full_lds_bytes(), s, p);
   return hipGetLastError();

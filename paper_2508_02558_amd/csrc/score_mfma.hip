@@ -253,17 +253,12 @@ static size_t score_lds_bytes(int group, int waves) { return (size_t)(group + wa
 template <int G>
 static hipError_t launch_g(const ScoreParams& p, hipStream_t s) {
   const size_t lds = score_lds_bytes(G, p.waves);
-  static bool attr_done = false;
-  if (!attr_done) {
-    const int max_lds = (int)score_lds_bytes(G, kMaxWavesPerWg);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_stats_mfma_kernel<G>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_cols_mfma_kernel<G>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOptIn lds_stats, lds_cols;
+  const int max_lds = (int)score_lds_bytes(G, kMaxWavesPerWg);
+  hipError_t e = lds_stats.ensure(reinterpret_cast<const void*>(score_stats_mfma_kernel<G>), max_lds);
+  if (e != hipSuccess) return e;
+  e = lds_cols.ensure(reinterpret_cast<const void*>(score_cols_mfma_kernel<G>), max_lds);
+  if (e != hipSuccess) return e;
   const dim3 grid(p.n_part, p.batch * p.hkv), block(p.waves * kWave);
   if (p.softmax && !p.skip_stats) hipLaunchKernelGGL(score_stats_mfma_kernel<G>, grid, block, lds, s, p);
   hipLaunchKernelGGL(score_cols_mfma_kernel<G>, grid, block, lds, s, p);

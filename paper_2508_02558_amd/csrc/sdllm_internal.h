@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace sdllm {
 
 constexpr int kWave = 64;            // CDNA wavefront
@@ -13,6 +15,27 @@ constexpr int kTileKeys = 32;        // keys per MFMA tile (one 32x32 block of l
 constexpr int kMaxWavesPerWg = 8;    // attention / scoring workgroups hold up to 8 waves
 constexpr int kNumCUs = 256;         // MI355X
 constexpr int kNumXCDs = 8;
+
+// Kernels that need more than the default 64 KB of dynamic LDS have to opt in, once per device (the
+// attribute belongs to the device's copy of the kernel).  One object per kernel remembers which
+// devices are done; concurrent host threads at worst both set the same value.
+class LdsOptIn {
+ public:
+  hipError_t ensure(const void* kernel, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 64;
+    const uint64_t bit = tracked ? uint64_t{1} << dev : 0;
+    if (tracked && (done_.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && tracked) done_.fetch_or(bit, std::memory_order_release);
+    return e;
+  }
+
+ private:
+  std::atomic<uint64_t> done_{0};
+};
 
 // One source of keys/values: rows of a [B, Hkv, n, d] tensor given by element strides.
 struct KvSegment {
