@@ -38,10 +38,14 @@ __device__ __forceinline__ void tile_logits_mma(const bf16x8 (&a)[8], const bf16
   for (int kk = 0; kk < 8; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], qf[kk], s, 0, 0, 0);
 }
 
-// Keys >= rows become -inf; returns the row max over the tile in the scaled log2 domain
-// (scale_log2 > 0), already exchanged between the halves.
+// Keys >= rows become -inf; returns the max over the 16 keys THIS half-lane holds, in the scaled
+// log2 domain (scale_log2 > 0).  The two halves of a row are only exchanged when tile_softmax finds
+// that the reference has to move.
 __device__ __forceinline__ float tile_mask_max(f32x16& s, int rows, float scale_log2, int half) {
   if (rows < kTileKeys) {   // only the last tile of a segment is ragged (wave-uniform)
+    // the empty asm keeps this a real branch: if-converted, the 32 compare/select instructions
+    // would run on every tile of kernels that are short of vector-ALU issue slots
+    asm volatile("");
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int key = half * 4 + (i >> 2) * 8 + (i & 3);
@@ -51,12 +55,11 @@ __device__ __forceinline__ float tile_mask_max(f32x16& s, int rows, float scale_
   float m_loc = s[0];
 #pragma unroll
   for (int i = 1; i < 16; ++i) m_loc = fmaxf(m_loc, s[i]);
-  m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
   return m_loc * scale_log2;
 }
 
-// Raw logits of one tile (unscaled; keys >= rows become -inf).  Returns the row max over the tile
-// in the scaled log2 domain.  All eight K fragments are requested before the first MFMA (the
+// Raw logits of one tile (unscaled; keys >= rows become -inf).  Returns this half-lane's max over the
+// tile in the scaled log2 domain.  All eight K fragments are requested before the first MFMA (the
 // scheduling barrier keeps the compiler from sinking each read next to its use, which would expose
 // the LDS latency eight times).
 __device__ __forceinline__ float tile_logits(const uint8_t* lds_k, const bf16x8 (&qf)[8], int rows, float scale_log2,
@@ -77,8 +80,10 @@ constexpr float kRescaleSlack = 8.f;
 
 __device__ __forceinline__ void tile_softmax(f32x16& s, float m_loc, float scale_log2, float& m_ref, float& l_run,
                                              f32x16 (&acc)[4]) {
+  // m_loc is per half-lane; the vote is over all 64 lanes, so either half exceeding moves both
   if (__ballot(m_loc > m_ref + kRescaleSlack) != 0) {   // wave-uniform; always taken on a wave's first tile
-    const float m_new = fmaxf(m_ref, m_loc);
+    const float m_row = fmaxf(m_loc, __shfl_xor(m_loc, 32));
+    const float m_new = fmaxf(m_ref, m_row);
     const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // exp2(-inf) = 0 on the first tile
     m_ref = m_new;
     l_run *= alpha;
