@@ -147,34 +147,6 @@ __device__ __forceinline__ void tile_pv(const uint8_t* lds_v, const f32x16& s, i
   tile_pv_mma(f, s, acc);
 }
 
-// NT whole tiles whose K and V are already in LDS (shared-stage kernels), software-pipelined over the
-// LDS latency: the V fragments of a tile are requested right after its logits MFMAs are issued (they
-// arrive under the softmax), and the K fragments of the NEXT tile right before this tile's PV MFMAs
-// are issued (they arrive under the PV product).  tile j: K at base + j*tile_stride, V kTileBytes on.
-template <int NT>
-__device__ __forceinline__ void tiles_pipelined(const uint8_t* base, int tile_stride, const bf16x8 (&qf)[8], int rows_left,
-                                                float scale_log2, int lane, float& m_ref, float& l_run, f32x16 (&acc)[4]) {
-  const int half = lane >> 5, col = lane & 31;
-  bf16x8 a[8];
-  tile_k_load(base, half, col, a);
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    const int rows = min(kTileKeys, rows_left - j * kTileKeys);
-    if (rows <= 0) break;
-    __builtin_amdgcn_sched_barrier(0);
-    f32x16 s;
-    tile_logits_mma(a, qf, s);
-    PvFrags f;
-    tile_pv_load(base + j * tile_stride + kTileBytes, lane, f);
-    __builtin_amdgcn_sched_barrier(0);
-    const float m_loc = tile_mask_max(s, rows, scale_log2, half);
-    tile_softmax(s, m_loc, scale_log2, m_ref, l_run, acc);
-    if (j + 1 < NT && rows_left - (j + 1) * kTileKeys > 0) tile_k_load(base + (j + 1) * tile_stride, half, col, a);
-    __builtin_amdgcn_sched_barrier(0);
-    tile_pv_mma(f, s, acc);
-  }
-}
-
 // Register (e, i) of a lane is output column 32e + 8*(i/4) + 4*half + i%4 of query row lane%32: four
 // consecutive registers are four consecutive columns.
 __device__ __forceinline__ int out_col0(int e, int i4, int half) { return 32 * e + 8 * i4 + 4 * half; }

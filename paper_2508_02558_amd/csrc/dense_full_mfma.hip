@@ -7,8 +7,12 @@
 //     (one 32x32 MFMA block, same fragment layout as the block-step kernels);
 //   * all L keys stream through a double-buffered LDS stage of two 32-key tiles, loaded once per
 //     workgroup with coalesced 16-byte loads and shared by the 8 waves: each K/V byte fetched from
-//     L2 feeds 256 query rows;
-//   * one workgroup barrier per 64 keys, the next stage's global loads in flight meanwhile;
+//     L2 feeds 256 query rows; one workgroup barrier per 64 keys, the next stage's global loads in
+//     flight meanwhile;
+//   * each wave alternates one block of sixteen MFMAs (logits of tile t+1 interleaved with the PV
+//     product of tile t) with one block of vector-ALU work (softmax of tile t+1), the LDS operand
+//     reads for the next MFMA block requested in between: while one wave of a SIMD is in its MFMA
+//     block the other one's softmax runs under it;
 //   * the query-block workgroups of one head (and of the G heads of a KV group) are adjacent in the
 //     grid and, after the XCD renumbering, share an L2.
 #include "attn_tile_math.h"
@@ -47,6 +51,34 @@ __device__ __forceinline__ void full_store_stage(uint8_t* stage, int tid, const 
   }
 }
 
+// One matrix-core block: the eight logits MFMAs of the NEXT tile (a dependent chain through sn) and the
+// eight PV MFMAs of the CURRENT tile (four independent accumulators), issued alternately so that no
+// MFMA waits for the one just before it.  A dependent MFMA stalls at the head of the SIMD's vector
+// issue port until its predecessor retires, and nothing of any wave gets past it meanwhile; spaced
+// two apart the sixteen run back to back and the other wave of the SIMD does its softmax under them.
+__device__ __forceinline__ void mfma_block(const bf16x8 (&a)[8], const bf16x8 (&qf)[8], f32x16& sn, const PvFrags& f,
+                                           const bf16x8 (&pb)[2], f32x16 (&acc)[4]) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sn[i] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], qf[i], sn, 0, 0, 0);
+    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[i >> 2][i & 3]), pb[i >> 2], acc[i & 3], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);   // the scheduler would otherwise group the dependent chain
+  }
+}
+
+// Softmax numerators of a tile's raw logits, packed to the bf16 B operands of its PV product.
+__device__ __forceinline__ void softmax_block(f32x16& sn, int rows, float scale_log2, int half, float& m_ref, float& l_run,
+                                              f32x16 (&acc)[4], bf16x8 (&pb)[2]) {
+  const float m_loc = tile_mask_max(sn, rows, scale_log2, half);
+  tile_softmax(sn, m_loc, scale_log2, m_ref, l_run, acc);
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pb[st][j] = (__bf16)sn[st * 8 + j];
+}
+
 __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFullParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   const int tid = threadIdx.x;
@@ -67,9 +99,10 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
   const int h = head - b * p.hq;
   const int g = h / p.group;
 
+  // rows past the end of the sequence compute on a copy of the last row and are not written back:
+  // every wave then runs the same program, barriers included
   const int q_row = qb * kFullRowsPerWg + wave * 32 + col;
   const bool row_valid = q_row < p.seq_len;
-  const bool wave_valid = qb * kFullRowsPerWg + wave * 32 < p.seq_len;
   const int q_row_c = row_valid ? q_row : p.seq_len - 1;
   bf16x8 qf[8];
   load_q_frags((const char*)p.q + 2 * (b * p.q_sb + h * p.q_sh + (int64_t)q_row_c * p.q_sr), half, qf);
@@ -80,6 +113,7 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
   const int n_keys = p.seq_len;
   const int stage_keys = kFullStageTiles * kTileKeys;
   const int nstages = (n_keys + stage_keys - 1) / stage_keys;
+  const int ntiles = (n_keys + kTileKeys - 1) / kTileKeys;
 
   f32x16 acc[4];
 #pragma unroll
@@ -88,22 +122,55 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
     for (int i = 0; i < 16; ++i) acc[e][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
+  // Pipeline state between iterations: pb = softmax numerators of the current tile t (bf16), f = its V
+  // fragments, a = the K fragments of tile t+1.  Iteration t issues one MFMA block (logits of t+1, PV
+  // of t), requests the fragments the next block needs from LDS, and runs the softmax of t+1 while
+  // they arrive.  Tile t lives in stage t/2; stage s+1 is published (and the barrier met) in the even
+  // iteration 2s, after the last read of stage s (V of tile 2s+1) has been requested and before the
+  // first read of stage s+1 (K of tile 2s+2).
   u32x4 kreg[kFullStageTiles], vreg[kFullStageTiles];
   full_load_stage(k_base, v_base, stride, 0, n_keys, tid, kreg, vreg);
   full_store_stage(smem, tid, kreg, vreg);
   __syncthreads();
+  if (nstages > 1) full_load_stage(k_base, v_base, stride, stage_keys, n_keys, tid, kreg, vreg);
 
-  for (int s = 0; s < nstages; ++s) {
-    if (s + 1 < nstages) full_load_stage(k_base, v_base, stride, (s + 1) * stage_keys, n_keys, tid, kreg, vreg);
+  bf16x8 a[8], pb[2];
+  PvFrags f;
+  f32x16 sn;
+  tile_k_load(smem, half, col, a);
+  __builtin_amdgcn_sched_barrier(0);
+  tile_logits_mma(a, qf, sn);
+  tile_pv_load(smem + kTileBytes, lane, f);
+  if (ntiles > 1) tile_k_load(smem + kFullKvTileBytes, half, col, a);
+  __builtin_amdgcn_sched_barrier(0);
+  softmax_block(sn, min(kTileKeys, n_keys), p.scale_log2, half, m_run, l_run, acc, pb);
+
+  for (int t = 0; t + 1 < ntiles; ++t) {   // t = current tile
+    const int s = t >> 1;
+    const bool even = (t & 1) == 0;
     const uint8_t* stage = smem + (s & 1) * kFullStageBytes;
-    if (wave_valid)
-      tiles_pipelined<kFullStageTiles>(stage, kFullKvTileBytes, qf, n_keys - s * stage_keys, p.scale_log2, lane, m_run,
-                                       l_run, acc);
-    if (s + 1 < nstages) full_store_stage(smem + ((s + 1) & 1) * kFullStageBytes, tid, kreg, vreg);
-    __syncthreads();
+    uint8_t* next_stage = smem + ((s + 1) & 1) * kFullStageBytes;
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_block(a, qf, sn, f, pb, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    // V of tile t+1: second tile of stage s (its last read) or first tile of stage s+1
+    tile_pv_load((even ? stage + kFullKvTileBytes : next_stage) + kTileBytes, lane, f);
+    if (even && s + 1 < nstages) {
+      full_store_stage(next_stage, tid, kreg, vreg);
+      __syncthreads();
+      if (s + 2 < nstages) full_load_stage(k_base, v_base, stride, (s + 2) * stage_keys, n_keys, tid, kreg, vreg);
+    }
+    // K of tile t+2: first or second tile of stage s+1
+    if (t + 2 < ntiles) tile_k_load(even ? next_stage : next_stage + kFullKvTileBytes, half, col, a);
+    __builtin_amdgcn_sched_barrier(0);
+    softmax_block(sn, min(kTileKeys, n_keys - (t + 1) * kTileKeys), p.scale_log2, half, m_run, l_run, acc, pb);
   }
+  // PV product of the last tile
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[i >> 2][i & 3]), pb[i >> 2], acc[i & 3], 0, 0, 0);
 
-  if (!wave_valid) return;
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   if (row_valid) {
     char* out_row = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + (int64_t)q_row * p.o_sr);

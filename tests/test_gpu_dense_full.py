@@ -31,6 +31,22 @@ def test_dense_attn_bf16_matches_oracle(Bt, Hq, Hkv, L):
     U.assert_close(out, U.oracle_attention_batch(q, k, v), "bf16", f"L={L}")
 
 
+@pytest.mark.parametrize("L", [31, 32, 64, 65, 96, 97, 128, 129, 191, 257])
+def test_dense_attn_tile_and_stage_boundaries(L):
+    # the kernel pipelines 32-key tiles through 64-key stages: every parity of tile and stage count,
+    # with and without a ragged last tile
+    print(f"[case] dense_attn boundaries L={L}", flush=True)
+    torch.manual_seed(1000 + L)
+    Bt, Hq, Hkv, d = 1, 2, 1, 128
+    q = torch.randn(Bt, Hq, L, d, device=DEV).bfloat16()
+    k = torch.randn(Bt, Hkv, L, d, device=DEV).bfloat16()
+    v = torch.randn(Bt, Hkv, L, d, device=DEV).bfloat16()
+    out = torch.zeros(Bt, Hq, L, d, device=DEV, dtype=torch.bfloat16)
+    B.sdllm_dense_attn(_shape(Bt, Hq, Hkv, d, L, B.SDLLM_BF16), q, k, v, out)
+    torch.cuda.synchronize()
+    U.assert_close(out, U.oracle_attention_batch(q, k, v), "bf16", f"L={L}")
+
+
 def test_dense_attn_generic_path_fp32_and_strided():
     print("[case] dense_attn fp32 / d=64 / strided", flush=True)
     torch.manual_seed(3)
