@@ -105,10 +105,14 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   pl.n_split = 1;
   pl.tiles_per_split = 0;
   pl.waves = 1;
-  // The shared-tile grouped-query kernel pays a workgroup barrier per tile; it wins once every CU has
-  // at least two query heads to serve (measured: B*Hq >= 512), below that one workgroup per head
-  // finishes sooner even though K/V are then read G times from L2.
-  pl.gqa = pl.mfma && attn_gqa_supports_group(s.n_q_heads / s.n_kv_heads) && s.batch * s.n_q_heads >= 2 * kNumCUs;
+  // Grouped-query heads: either one workgroup per query head (K/V then come G times out of L2, but the
+  // eight waves of a head split its keys and merge in LDS) or the shared-tile kernel (K/V read once,
+  // one wave per head, key splits merged through fp32 partials and a second launch).  Measured on
+  // MI355X (G = 7, 2, 4; batch 1-32; 2k-17k keys) the shared-tile kernel wins once there are about
+  // 30 000 wave-tiles of work (heads x 32-key tiles), whatever the mix of heads and keys.
+  const int all_tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
+  pl.gqa = pl.mfma && attn_gqa_supports_group(s.n_q_heads / s.n_kv_heads) &&
+           (int64_t)s.batch * s.n_q_heads * all_tiles >= 30000;
   if (pl.gqa) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int rows = s.batch * s.n_kv_heads;

@@ -1,72 +1,117 @@
 // Grouped-query variant of the bf16 MFMA block attention (Alg. 3, cache_state == 2, and the dense
 // block rows of states 0/1) for models whose G query heads share one KV head (2 <= G <= 8).
 //
-// One workgroup serves one (batch, KV head) and a range of key tiles; wave w is query head
-// g*G + w.  The K/V tiles are loaded ONCE per workgroup, cooperatively and fully coalesced, into a
-// double-buffered LDS stage of one 32-key tile (K and V: 18.5 KB), and all G waves run their own
-// logits / online softmax / PV product against the same stage, so K and V leave HBM (and L2) once
-// however many query heads read them.  One workgroup barrier per tile; the next tile's global
-// loads are in flight while the current one is computed.  Each wave owns its head's result, so there
-// is no cross-wave merge; key splits write fp32 partials for the combine kernel.
+// A workgroup serves one (batch, KV head), a range of key tiles and W of the group's query heads
+// (wave w = one head).  The K/V tiles are loaded ONCE per workgroup, cooperatively and fully coalesced,
+// into a double-buffered LDS stage (two 32-key tiles of K and V with 4 waves, one tile with fewer, so
+// that the staging registers stay at 32 per lane), and all W waves run against the same stage.
+// With several heads per key the kernel is bound by the matrix and vector pipes rather than by HBM, and
+// each wave runs the software pipeline of the full-sequence kernel: one block of sixteen MFMAs (logits
+// of tile j+1 interleaved with the PV product of tile j), the LDS fragment requests for the next
+// block, then the softmax of tile j+1.
+// Groups of 4 to 8 heads are served by TWO workgroups of ceil(G/2) waves that stream the same keys:
+// a CU holds 8 such waves either way, but two workgroups keep two stages of global loads in flight
+// and one's load latency hides under the other's arithmetic (one 7- or 8-wave workgroup per CU spent
+// a third of its time waiting for its single stage).  The pair is given linear workgroup ids 8 apart,
+// so both land on the same XCD and the second read of a K/V line is an L2 hit.
+// Each wave owns its head's result, so there is no cross-wave merge; key splits write fp32 partials
+// for the combine kernel.
 #include "attn_tile_math.h"
 
 namespace sdllm {
 
-constexpr int kStageBytes = kTileBytes + kVTileBytes;   // one 32-key tile: K, V
-constexpr int kTileChunks = 512;              // 16-byte pieces of one tensor of a tile
-constexpr int kMaxStageIters = 4;             // pieces per thread and tensor with the fewest threads (G = 2)
+constexpr int kKvTileBytes = kTileBytes + kVTileBytes;   // one 32-key tile: K, V
+constexpr int kTileChunks = 512;                         // 16-byte pieces of one tensor of a tile
 
-size_t attn_gqa_lds_bytes() { return 2 * (size_t)kStageBytes; }
+constexpr int gqa_stage_tiles(int waves) { return waves >= 4 ? 2 : 1; }
+constexpr int gqa_chunks(int waves) { return (kTileChunks + waves * kWave - 1) / (waves * kWave); }   // per thread, tensor and tile
+constexpr size_t gqa_lds_bytes(int waves) { return 2 * (size_t)gqa_stage_tiles(waves) * kKvTileBytes; }
+constexpr int gqa_head_splits(int group) { return group >= 4 ? 2 : 1; }
 
-// K and V of one tile into registers, all threads of the workgroup together: piece c = tid + j*T is
-// 16-byte chunk c%16 of row c/16.  The tile base is workgroup-uniform and K and V share offsets.
-__device__ __forceinline__ void load_stage(const TileSrc& ts, uint32_t stride, int tid, int nthreads,
-                                           u32x4 (&kreg)[kMaxStageIters], u32x4 (&vreg)[kMaxStageIters]) {
+// Stage `stage_idx` of this workgroup's tile range into registers, all threads together: piece
+// c = tid + i*T of a tile is 16-byte chunk c%16 of row c/16.  A tile never straddles the two key
+// segments, so its base is workgroup-uniform and K and V share offsets.
+template <int W>
+__device__ __forceinline__ void gqa_load_stage(const SegPtrs& sp, int first_tile, int t_end, int tid,
+                                               u32x4 (&kreg)[gqa_stage_tiles(W) * gqa_chunks(W)],
+                                               u32x4 (&vreg)[gqa_stage_tiles(W) * gqa_chunks(W)]) {
+  constexpr int NT = gqa_stage_tiles(W), CH = gqa_chunks(W), T = W * kWave;
 #pragma unroll
-  for (int j = 0; j < kMaxStageIters; ++j) {
-    const int c = tid + j * nthreads;
-    if (c < kTileChunks) {
-      int r = c >> 4;
-      r = r < ts.rows ? r : ts.rows - 1;       // rows past the end re-read the last key; masked later
-      const uint32_t off = (uint32_t)r * stride + ((c & 15) << 4);
-      kreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.k + off));
-      vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.v + off));
+  for (int j = 0; j < NT; ++j) {
+    if (first_tile + j >= t_end) break;      // workgroup-uniform
+    uint32_t stride;
+    const TileSrc ts = tile_src(sp, first_tile + j, stride);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int c = tid + i * T;
+      if (CH * T == kTileChunks || c < kTileChunks) {
+        int r = c >> 4;
+        r = r < ts.rows ? r : ts.rows - 1;   // rows past the end re-read the last key; masked later
+        const uint32_t off = (uint32_t)r * stride + ((c & 15) << 4);
+        kreg[j * CH + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.k + off));
+        vreg[j * CH + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.v + off));
+      }
     }
   }
 }
 
-__device__ __forceinline__ void store_stage(uint8_t* stage, int tid, int nthreads, const u32x4 (&kreg)[kMaxStageIters],
-                                            const u32x4 (&vreg)[kMaxStageIters]) {
+template <int W>
+__device__ __forceinline__ void gqa_store_stage(uint8_t* stage, int tid, const u32x4 (&kreg)[gqa_stage_tiles(W) * gqa_chunks(W)],
+                                                const u32x4 (&vreg)[gqa_stage_tiles(W) * gqa_chunks(W)]) {
+  constexpr int NT = gqa_stage_tiles(W), CH = gqa_chunks(W), T = W * kWave;
 #pragma unroll
-  for (int j = 0; j < kMaxStageIters; ++j) {
-    const int c = tid + j * nthreads;
-    if (c < kTileChunks) {
-      *reinterpret_cast<u32x4*>(stage + tile_off(c >> 4, c & 15)) = kreg[j];
-      *reinterpret_cast<u32x4*>(stage + kTileBytes + vtile_off(c >> 4, c & 15)) = vreg[j];
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int c = tid + i * T;
+      if (CH * T == kTileChunks || c < kTileChunks) {
+        *reinterpret_cast<u32x4*>(stage + j * kKvTileBytes + tile_off(c >> 4, c & 15)) = kreg[j * CH + i];
+        *reinterpret_cast<u32x4*>(stage + j * kKvTileBytes + kTileBytes + vtile_off(c >> 4, c & 15)) = vreg[j * CH + i];
+      }
     }
-  }
 }
 
-template <int NSEG>
-__global__ __launch_bounds__(512) void attn_gqa_mfma_bf16_kernel(const AttnParams p) {
+// two waves per SIMD (256 registers each) whatever the workgroup size: a CU has to hold 8 of these waves
+template <int NSEG, int W>
+__global__ __launch_bounds__(W * kWave) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
+  constexpr int NT = gqa_stage_tiles(W);
+  constexpr int kStageBytes = NT * kKvTileBytes;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   const int tid = threadIdx.x;
-  const int nthreads = blockDim.x;
   const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // query head within the group
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int half = lane >> 5;
   const int col = lane & 31;
-  const int split = blockIdx.x;
-  const int bg = blockIdx.y;
+
+  // linear id -> (key split, batch * KV head, head split); the two head splits of a pair sit 8 ids
+  // apart (same XCD under round-robin dispatch) whenever the grid is a multiple of 16
+  const int lid = blockIdx.x;
+  int pair = lid, hs = 0;
+  if (head_splits == 2) {
+    if ((gridDim.x & 15) == 0) {
+      hs = (lid >> 3) & 1;
+      pair = ((lid >> 4) << 3) | (lid & 7);
+    } else {
+      hs = lid & 1;
+      pair = lid >> 1;
+    }
+  }
+  const int split = pair % p.n_split;
+  const int bg = pair / p.n_split;
   const int b = bg / p.hkv;
   const int g = bg - b * p.hkv;
-  const int h = g * p.group + wave;
+  // a wave past the end of the group (odd G) takes part in staging and barriers only
+  const int hg = hs * W + wave;
+  const bool head_valid = hg < p.group;
+  const int h = g * p.group + (head_valid ? hg : p.group - 1);
   const int head = b * p.hq + h;
 
   const SegPtrs sp = seg_ptrs(p, b, g, NSEG == 2);
   const int ntiles = sp.tiles0 + (sp.n1 + kTileKeys - 1) / kTileKeys;
   const int t_begin = split * p.tiles_per_split;
   const int t_end = min(ntiles, t_begin + p.tiles_per_split);
+  const int nt = t_end - t_begin;            // >= 1: the planner leaves no split empty
+  const int nstages = (nt + NT - 1) / NT;
 
   bf16x8 qf[8];
   load_q_frags((const char*)p.q + 2 * (b * p.q_sb + h * p.q_sh + col * p.q_sr), half, qf);
@@ -78,31 +123,67 @@ __global__ __launch_bounds__(512) void attn_gqa_mfma_bf16_kernel(const AttnParam
     for (int i = 0; i < 16; ++i) acc[e][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  u32x4 kreg[kMaxStageIters], vreg[kMaxStageIters];
-  uint32_t stride = 0;
-  TileSrc ts = tile_src(sp, t_begin, stride);
-  load_stage(ts, stride, tid, nthreads, kreg, vreg);
-  store_stage(smem, tid, nthreads, kreg, vreg);
-  int rows = ts.rows;
+  // valid keys of local tile j (only the last tile of a segment is ragged)
+  auto rows_of = [&](int j) {
+    const int t = t_begin + j;
+    return t < sp.tiles0 ? min(kTileKeys, sp.n0 - t * kTileKeys) : min(kTileKeys, sp.n1 - (t - sp.tiles0) * kTileKeys);
+  };
+  // LDS address of local tile j: stage j / NT (double-buffered), slot j % NT
+  auto tile_lds = [&](int j) { return smem + ((j / NT) & 1) * kStageBytes + (j % NT) * kKvTileBytes; };
+
+  u32x4 kreg[NT * gqa_chunks(W)], vreg[NT * gqa_chunks(W)];
+  gqa_load_stage<W>(sp, t_begin, t_end, tid, kreg, vreg);
+  gqa_store_stage<W>(smem, tid, kreg, vreg);
+  if (nstages > 1) gqa_load_stage<W>(sp, t_begin + NT, t_end, tid, kreg, vreg);
   __syncthreads();
 
-  for (int t = t_begin; t < t_end; ++t) {
-    const bool more = t + 1 < t_end;
-    if (more) {
-      ts = tile_src(sp, t + 1, stride);
-      load_stage(ts, stride, tid, nthreads, kreg, vreg);   // in flight while this tile is computed
+  // Pipeline state between iterations: pb = softmax numerators of the current tile j (bf16), f = its V
+  // fragments, a = the K fragments of tile j+1.  After the MFMA block of iteration j the wave requests
+  // V of tile j+1 and K of tile j+2.  When tile j+2 opens a new stage k, that stage is published first
+  // (registers -> LDS, workgroup barrier): the V request just made was this wave's last read of stage
+  // k-1, and the buffer being overwritten held stage k-2, whose last read every wave had requested
+  // before the previous publication's barrier.
+  bf16x8 a[8], pb[2];
+  PvFrags f;
+  f32x16 sn;
+
+  auto after_mfma = [&](int j) {   // j = current tile (-1 in the prologue)
+    if (head_valid) tile_pv_load(tile_lds(j + 1) + kTileBytes, lane, f);
+    if (j + 2 < nt && (j + 2) % NT == 0) {
+      const int s_new = (j + 2) / NT;
+      gqa_store_stage<W>(smem + (s_new & 1) * kStageBytes, tid, kreg, vreg);
+      __syncthreads();
+      if (s_new + 1 < nstages) gqa_load_stage<W>(sp, t_begin + (s_new + 1) * NT, t_end, tid, kreg, vreg);
     }
-    const uint8_t* stage = smem + ((t - t_begin) & 1) * kStageBytes;
-    f32x16 sc;
-    const float m_loc = tile_logits(stage, qf, rows, p.scale_log2, half, col, sc);
-    tile_softmax(sc, m_loc, p.scale_log2, m_run, l_run, acc);
-    tile_pv(stage + kTileBytes, sc, lane, acc);
-    if (more) {
-      store_stage(smem + ((t + 1 - t_begin) & 1) * kStageBytes, tid, nthreads, kreg, vreg);
-      rows = ts.rows;
-    }
-    __syncthreads();
+    if (!head_valid) return;
+    if (j + 2 < nt) tile_k_load(tile_lds(j + 2), half, col, a);
+    __builtin_amdgcn_sched_barrier(0);
+    softmax_block(sn, rows_of(j + 1), p.scale_log2, half, m_run, l_run, acc, pb);
+  };
+
+  // a wave past the end of the group (odd G) only stages and synchronises
+  if (head_valid) {
+    tile_k_load(smem, half, col, a);
+    __builtin_amdgcn_sched_barrier(0);
+    tile_logits_mma(a, qf, sn);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  after_mfma(-1);
+
+  for (int j = 0; j + 1 < nt; ++j) {
+    if (head_valid) {
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_block(a, qf, sn, f, pb, acc);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    after_mfma(j);
+  }
+  if (!head_valid) return;
+  // PV product of the last tile
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[i >> 2][i & 3]), pb[i >> 2], acc[i & 3], 0, 0, 0);
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const size_t slot = (size_t)head * p.n_split + split;
@@ -111,14 +192,25 @@ __global__ __launch_bounds__(512) void attn_gqa_mfma_bf16_kernel(const AttnParam
                     p.part_ml + slot * 64);
 }
 
+template <int NSEG, int W>
+static hipError_t launch_w(const AttnParams& p, int head_splits, hipStream_t s) {
+  static LdsOptIn lds;
+  const hipError_t e = lds.ensure(reinterpret_cast<const void*>(attn_gqa_mfma_bf16_kernel<NSEG, W>), (int)gqa_lds_bytes(W));
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((attn_gqa_mfma_bf16_kernel<NSEG, W>), dim3(p.n_split * p.batch * p.hkv * head_splits), dim3(W * kWave),
+                     gqa_lds_bytes(W), s, p, head_splits);
+  return hipGetLastError();
+}
+
 template <int NSEG>
 static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
-  static LdsOptIn lds;
-  const hipError_t e = lds.ensure(reinterpret_cast<const void*>(attn_gqa_mfma_bf16_kernel<NSEG>), (int)attn_gqa_lds_bytes());
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_gqa_mfma_bf16_kernel<NSEG>, dim3(p.n_split, p.batch * p.hkv), dim3(p.group * kWave),
-                     attn_gqa_lds_bytes(), s, p);
-  return hipGetLastError();
+  const int hs = gqa_head_splits(p.group);
+  switch ((p.group + hs - 1) / hs) {   // waves per workgroup
+    case 2: return launch_w<NSEG, 2>(p, hs, s);
+    case 3: return launch_w<NSEG, 3>(p, hs, s);
+    case 4: return launch_w<NSEG, 4>(p, hs, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 bool attn_gqa_supports_group(int group) { return group >= 2 && group <= 8; }

@@ -66,27 +66,68 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const AttnParams p) {
   }
 }
 
-// Merge the n_split partial (max, sum, numerator) triples of each query row.
-// grid: (nq, B*Hq), block: d threads.
+// Merge the n_split partial (max, sum, numerator) triples of each query row: one thread per
+// (row, four output columns), 16-byte loads, four splits' loads issued before they are used (the
+// partials mostly sit in L2 / MALL, so the merge is bound by how many loads are in flight).
+// block: kCombineThreads threads = kCombineThreads * 4 / d consecutive rows of the [B*Hq, nq] row list.
+constexpr int kCombineThreads = 256;
+typedef __attribute__((ext_vector_type(4))) float cf32x4;
+
 template <typename T>
-__global__ void attn_combine_kernel(const AttnParams p) {
-  const int row = blockIdx.x;
-  const int head = blockIdx.y;
-  const int t = threadIdx.x;
+__global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const AttnParams p, const int total_rows) {
+  const int per_row = p.d >> 2;                                   // threads per row
+  const int item = blockIdx.x * kCombineThreads + threadIdx.x;
+  const int grow = item / per_row;                                // index into the [B*Hq, nq] row list
+  if (grow >= total_rows) return;
+  const int c4 = (item - grow * per_row) << 2;
+  const int head = grow / p.nq;
+  const int row = grow - head * p.nq;
   const int b = head / p.hq;
   const int h = head - b * p.hq;
-  const size_t slot0 = (size_t)head * p.n_split;
+  const float* ml = p.part_ml + (size_t)head * p.n_split * 2 * p.nq + row;        // split stride 2*nq
+  const float* po = p.part_o + ((size_t)head * p.n_split * p.nq + row) * p.d + c4;   // split stride nq*d
+  const int ml_ss = 2 * p.nq;
+  const size_t po_ss = (size_t)p.nq * p.d;
+
   float m_tot = -INFINITY;
-  for (int s = 0; s < p.n_split; ++s) m_tot = fmaxf(m_tot, p.part_ml[(slot0 + s) * 2 * p.nq + row]);
-  float l_tot = 0.f, o = 0.f;
-  for (int s = 0; s < p.n_split; ++s) {
-    const float m_s = p.part_ml[(slot0 + s) * 2 * p.nq + row];
-    const float f = (m_s == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_s - m_tot);
-    l_tot += f * p.part_ml[(slot0 + s) * 2 * p.nq + p.nq + row];
-    o += f * p.part_o[((slot0 + s) * p.nq + row) * p.d + t];
+#pragma unroll 4
+  for (int s = 0; s < p.n_split; ++s) m_tot = fmaxf(m_tot, ml[s * ml_ss]);
+  float l_tot = 0.f;
+  cf32x4 o = {0.f, 0.f, 0.f, 0.f};
+  int s = 0;
+  for (; s + 4 <= p.n_split; s += 4) {
+    float m_s[4], l_s[4];
+    cf32x4 o_s[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      m_s[u] = ml[(s + u) * ml_ss];
+      l_s[u] = ml[(s + u) * ml_ss + p.nq];
+      o_s[u] = *reinterpret_cast<const cf32x4*>(po + (s + u) * po_ss);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float f = (m_s[u] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_s[u] - m_tot);
+      l_tot += f * l_s[u];
+      o += f * o_s[u];
+    }
   }
-  T* out = (T*)p.out + b * p.o_sb + h * p.o_sh + row * p.o_sr;
-  out[t] = (T)(o / l_tot);
+  for (; s < p.n_split; ++s) {
+    const float m_s = ml[s * ml_ss];
+    const float f = (m_s == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_s - m_tot);
+    l_tot += f * ml[s * ml_ss + p.nq];
+    o += f * *reinterpret_cast<const cf32x4*>(po + s * po_ss);
+  }
+  const float inv = 1.f / l_tot;
+  T* out = (T*)p.out + b * p.o_sb + h * p.o_sh + row * p.o_sr + c4;
+  if constexpr (sizeof(T) == 2) {
+    typedef __attribute__((ext_vector_type(4))) __bf16 cbf16x4;
+    cbf16x4 v;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) v[r] = (__bf16)(o[r] * inv);
+    *reinterpret_cast<cbf16x4*>(out) = v;      // rows and row strides are 16-byte aligned, c4 a multiple of 4
+  } else {
+    *reinterpret_cast<cf32x4*>(out) = o * inv;
+  }
 }
 
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, hipStream_t s) {
@@ -102,9 +143,11 @@ hipError_t launch_attn_simple(const AttnParams& p, int dtype, hipStream_t s) {
 }
 
 hipError_t launch_attn_combine(const AttnParams& p, int dtype, hipStream_t s) {
-  const dim3 grid(p.nq, p.batch * p.hq);
-  if (dtype == 0) hipLaunchKernelGGL(attn_combine_kernel<__bf16>, grid, dim3(p.d), 0, s, p);
-  else hipLaunchKernelGGL(attn_combine_kernel<float>, grid, dim3(p.d), 0, s, p);
+  const int total_rows = p.batch * p.hq * p.nq;
+  const int64_t items = (int64_t)total_rows * (p.d >> 2);
+  const dim3 grid((unsigned)((items + kCombineThreads - 1) / kCombineThreads));
+  if (dtype == 0) hipLaunchKernelGGL(attn_combine_kernel<__bf16>, grid, dim3(kCombineThreads), 0, s, p, total_rows);
+  else hipLaunchKernelGGL(attn_combine_kernel<float>, grid, dim3(kCombineThreads), 0, s, p, total_rows);
   return hipGetLastError();
 }
 

@@ -147,6 +147,35 @@ __device__ __forceinline__ void tile_pv(const uint8_t* lds_v, const f32x16& s, i
   tile_pv_mma(f, s, acc);
 }
 
+// ---- software-pipelined form (kernels whose tiles sit in shared LDS stages) ----
+// One matrix-core block: the eight logits MFMAs of the NEXT tile (a dependent chain through sn) and the
+// eight PV MFMAs of the CURRENT tile (four independent accumulators), issued alternately so that no
+// MFMA waits for the one just before it.  A dependent MFMA stalls at the head of the SIMD's vector
+// issue port until its predecessor retires, and nothing of any wave gets past it meanwhile; spaced
+// two apart the sixteen run back to back and the other wave of the SIMD does its softmax under them.
+__device__ __forceinline__ void mfma_block(const bf16x8 (&a)[8], const bf16x8 (&qf)[8], f32x16& sn, const PvFrags& f,
+                                           const bf16x8 (&pb)[2], f32x16 (&acc)[4]) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sn[i] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], qf[i], sn, 0, 0, 0);
+    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[i >> 2][i & 3]), pb[i >> 2], acc[i & 3], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);   // the scheduler would otherwise group the dependent chain
+  }
+}
+
+// Softmax numerators of a tile's raw logits, packed to the bf16 B operands of its PV product.
+__device__ __forceinline__ void softmax_block(f32x16& sn, int rows, float scale_log2, int half, float& m_ref, float& l_run,
+                                              f32x16 (&acc)[4], bf16x8 (&pb)[2]) {
+  const float m_loc = tile_mask_max(sn, rows, scale_log2, half);
+  tile_softmax(sn, m_loc, scale_log2, m_ref, l_run, acc);
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pb[st][j] = (__bf16)sn[st * 8 + j];
+}
+
 // Register (e, i) of a lane is output column 32e + 8*(i/4) + 4*half + i%4 of query row lane%32: four
 // consecutive registers are four consecutive columns.
 __device__ __forceinline__ int out_col0(int e, int i4, int half) { return 32 * e + 8 * i4 + 4 * half; }

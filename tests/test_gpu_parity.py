@@ -224,17 +224,27 @@ def test_scores_match_oracle_values():
                 np.testing.assert_allclose(pg, pooled_orc, rtol=0, atol=2e-5)
 
 
+GQA_SHARED_KERNEL_WAVE_TILES = 30000   # plan_attn (csrc/api.hip): heads x 32-key tiles from which the shared-tile kernel runs
+
+
+def _batch_for_shared_kernel(n_q_heads, n_keys_sparse):
+    tiles = -(-n_keys_sparse // 32) + 1            # cache tiles + the block's own tile
+    return -(-GQA_SHARED_KERNEL_WAVE_TILES // (n_q_heads * tiles)) + 1
+
+
 def test_grouped_query_kernel_at_large_batch():
-    # B*Hq >= 512 switches sdllm_sparse_attn / the dense step to the shared-tile grouped-query kernel
+    # enough heads x key tiles switches sdllm_sparse_attn / the dense step to the shared-tile grouped-query kernel
     _note("[case] grouped-query shared-tile kernel")
-    w = wl.WORKLOADS["dream7b_gqa"].scaled(batch=19, prompt=300, gen=64)     # 532 query heads, ragged tiles
+    w = wl.WORKLOADS["dream7b_gqa"].scaled(prompt=300, gen=64)               # ragged tiles; 150 + 16 retained keys
+    w = w.scaled(batch=_batch_for_shared_kernel(w.n_q_heads, 166))
     inp = wl.make_block_inputs(w, n_steps=3, device=DEV)
     shape = U.shape_for(w)
     gl = U.GpuLayer(shape, DEV)
+    assert gl.k_total == 166
     o, b = inp["block_off"], w.block
     q1 = inp["q"][1].contiguous()
     assert gl.block_step(1, 1, q1, inp["k_full"], inp["v_full"]) == 1
-    bs = [0, 7, 18]
+    bs = [0, 7, w.batch - 1]
     U.assert_close(gl.out[bs], U.oracle_attention_batch(q1[bs], inp["k_full"][bs], inp["v_full"][bs]), "bf16", "dense gqa")
     q2, kb, vb = inp["q"][2].contiguous(), inp["k_blk"][2].contiguous(), inp["v_blk"][2].contiguous()
     assert gl.block_step(2, 1, q2, kb, vb) == 2
@@ -242,13 +252,26 @@ def test_grouped_query_kernel_at_large_batch():
     ref = U.oracle_attention_batch(q2[bs], torch.cat([gl.k_cache[bs, :, :kt], kb[bs]], 2),
                                    torch.cat([gl.v_cache[bs, :, :kt], vb[bs]], 2))
     U.assert_close(gl.out[bs], ref, "bf16", "sparse gqa")
-    for G, Hkv in ((2, 3), (8, 1)):
-        w2 = w.scaled(batch=600 // (G * Hkv) + 1, n_q_heads=G * Hkv, n_kv_heads=Hkv, prompt=70, gen=64)
-        inp2 = wl.make_block_inputs(w2, n_steps=1, device=DEV)
+    del inp, gl
+    # every group size has its own workgroup shape (waves, pieces per thread, tiles per LDS stage, one
+    # or two head splits); prompts chosen so that tile counts are odd and even, with ragged last tiles
+    for G, Hkv, prompt in ((2, 3, 70), (3, 2, 33), (4, 2, 130), (5, 1, 100), (6, 1, 257), (7, 1, 64), (8, 1, 70)):
+        w2 = w.scaled(n_q_heads=G * Hkv, n_kv_heads=Hkv, prompt=prompt, gen=64)
+        w2 = w2.scaled(batch=_batch_for_shared_kernel(G * Hkv, -(-prompt // 2) + 16))
+        inp2 = wl.make_block_inputs(w2, n_steps=3, device=DEV)
         gl2 = U.GpuLayer(U.shape_for(w2), DEV)
-        q = inp2["q"][0].contiguous()
-        gl2.block_step(0, 1, q, inp2["k_full"], inp2["v_full"])
-        U.assert_close(gl2.out[:2], U.oracle_attention_batch(q[:2], inp2["k_full"][:2], inp2["v_full"][:2]), "bf16", f"G={G}")
+        q = inp2["q"][1].contiguous()
+        gl2.block_step(1, 1, q, inp2["k_full"], inp2["v_full"])
+        last = w2.batch - 1
+        bs2 = [0, last]
+        U.assert_close(gl2.out[bs2], U.oracle_attention_batch(q[bs2], inp2["k_full"][bs2], inp2["v_full"][bs2]), "bf16", f"dense G={G}")
+        q2, kb, vb = inp2["q"][2].contiguous(), inp2["k_blk"][2].contiguous(), inp2["v_blk"][2].contiguous()
+        gl2.block_step(2, 1, q2, kb, vb)
+        kt = gl2.k_total
+        ref = U.oracle_attention_batch(q2[bs2], torch.cat([gl2.k_cache[bs2, :, :kt], kb[bs2]], 2),
+                                       torch.cat([gl2.v_cache[bs2, :, :kt], vb[bs2]], 2))
+        U.assert_close(gl2.out[bs2], ref, "bf16", f"sparse G={G}")
+        del inp2, gl2
 
 
 def test_block_step_replays_identically_from_a_hip_graph():
