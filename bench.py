@@ -42,27 +42,34 @@ def measured_traffic(workload: str):
 
 
 def cpu_baseline(w, inp0, n_batch, threads_note):
-    """The float64 oracle on one layer's block, `n_batch` batch elements, all 32 steps."""
+    """The float64 oracle on one layer's block, `n_batch` batch elements, all 32 steps (BLAS threads as
+    the box gives them), plus the same on one batch element with BLAS pinned to one thread."""
     import numpy as np
-    from threadpoolctl import threadpool_info
+    from threadpoolctl import threadpool_info, threadpool_limits
 
     from oracle import sdllm_oracle as orc
     from paper_2508_02558_amd import workloads as wl
 
     o, b = inp0["block_off"], w.block
-    t0 = time.perf_counter()
-    for bi in range(n_batch):
-        k_full = wl.to_f64(inp0["k_full"][bi])
-        v_full = wl.to_f64(inp0["v_full"][bi])
-        cache = {}
-        for t in range(w.steps_per_block):
-            q = wl.to_f64(inp0["q"][t, bi])
-            if orc.cache_state(t, 1) < 2:
-                orc.block_step(t, 1, q, k_full, v_full, cache, block_off=o, block_len=b, r=w.retention, s=w.pool_kernel)
-            else:
-                orc.block_step(t, 1, q, wl.to_f64(inp0["k_blk"][t, bi]), wl.to_f64(inp0["v_blk"][t, bi]), cache,
-                               block_off=o, block_len=b, r=w.retention, s=w.pool_kernel)
-    dt = time.perf_counter() - t0
+
+    def run(batch_elems):
+        t0 = time.perf_counter()
+        for bi in range(batch_elems):
+            k_full = wl.to_f64(inp0["k_full"][bi])
+            v_full = wl.to_f64(inp0["v_full"][bi])
+            cache = {}
+            for t in range(w.steps_per_block):
+                q = wl.to_f64(inp0["q"][t, bi])
+                if orc.cache_state(t, 1) < 2:
+                    orc.block_step(t, 1, q, k_full, v_full, cache, block_off=o, block_len=b, r=w.retention, s=w.pool_kernel)
+                else:
+                    orc.block_step(t, 1, q, wl.to_f64(inp0["k_blk"][t, bi]), wl.to_f64(inp0["v_blk"][t, bi]), cache,
+                                   block_off=o, block_len=b, r=w.retention, s=w.pool_kernel)
+        return time.perf_counter() - t0
+
+    dt = run(n_batch)
+    with threadpool_limits(limits=1, user_api="blas"):
+        dt1 = run(1)
     # one sdllm_block_step call covers the whole batch of one layer for one denoising step
     calls_equiv = w.steps_per_block * n_batch / w.batch
     blas = [p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"]
@@ -71,6 +78,8 @@ def cpu_baseline(w, inp0, n_batch, threads_note):
         "kind": "oracle",
         "sample": f"one layer, {n_batch} of {w.batch} batch elements, all {w.steps_per_block} denoising steps of one "
                   f"block ({dt:.1f} s of CPU work), scaled to the full batch",
+        "single_thread": {"value": w.steps_per_block / w.batch / dt1, "unit": "block-steps/s per layer", "cores": 1,
+                          "sample": f"one batch element, all {w.steps_per_block} steps ({dt1:.1f} s), scaled to the full batch"},
     }
 
 
@@ -206,6 +215,10 @@ def main() -> int:
     elapsed = t1 - t0
     calls = args.steps * T * n_layers
     sparse_launch_us = 1e3 * sum(sparse_ms) / (len(sparse_ms) * n_layers) if sparse_ms else float("nan")
+    # spread over the timed all-layer sweeps (each sample = one sweep's HIP-event time / layers)
+    per_sweep = sorted(1e3 * m / n_layers for m in sparse_ms)
+    pct = lambda q: per_sweep[min(len(per_sweep) - 1, int(q * len(per_sweep)))] if per_sweep else float("nan")
+    sparse_spread = {"samples": len(per_sweep), "p10_us": pct(0.10), "p50_us": pct(0.50), "p90_us": pct(0.90)}
     bytes_sparse = attn_bytes(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, k_total + b, b, esize)
     achieved = bytes_sparse / (sparse_launch_us * 1e-6) / 1e9 if sparse_ms else float("nan")
 
@@ -320,6 +333,7 @@ def main() -> int:
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "kernel": "attn_mfma_bf16_kernel (sdllm_sparse_attn, cache_state 2)",
                      "algorithmic_bytes_per_launch": bytes_sparse, "avg_launch_us": sparse_launch_us,
+                     "launch_us_spread": sparse_spread,
                      "streaming_read_ceiling": {"us_for_same_bytes": probe_us, "GB/s": read_ceiling_gbs,
                                                 "achieved_over_ceiling": achieved / read_ceiling_gbs}},
         # the comparator the workload names: a dense full-cache scheme pays the dense block-row attention
