@@ -73,7 +73,8 @@ __device__ __forceinline__ void gqa_store_stage(uint8_t* stage, int tid, const u
 
 // two waves per SIMD (256 registers each) whatever the workgroup size: a CU has to hold 8 of these waves
 template <int NSEG, int W>
-__global__ __launch_bounds__(W * kWave) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
+__global__ __launch_bounds__(W * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
   constexpr int NT = gqa_stage_tiles(W);
   constexpr int kStageBytes = NT * kKvTileBytes;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -181,9 +182,7 @@ __global__ __launch_bounds__(W * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)
   if (!head_valid) return;
   // PV product of the last tile
   __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[i >> 2][i & 3]), pb[i >> 2], acc[i & 3], 0, 0, 0);
+  pv_block(f, pb, acc);
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const size_t slot = (size_t)head * p.n_split + split;

@@ -160,9 +160,18 @@ __device__ __forceinline__ void mfma_block(const bf16x8 (&a)[8], const bf16x8 (&
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], qf[i], sn, 0, 0, 0);
-    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[i >> 2][i & 3]), pb[i >> 2], acc[i & 3], 0, 0, 0);
+    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[i >> 2][i & 3]), pb[i >> 2],
+                                                         acc[i & 3], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);   // the scheduler would otherwise group the dependent chain
   }
+}
+
+// The PV product alone (last tile of a pipeline: no next tile's logits to pair it with).
+__device__ __forceinline__ void pv_block(const PvFrags& f, const bf16x8 (&pb)[2], f32x16 (&acc)[4]) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[i >> 2][i & 3]), pb[i >> 2],
+                                                         acc[i & 3], 0, 0, 0);
 }
 
 // Softmax numerators of a tile's raw logits, packed to the bf16 B operands of its PV product.

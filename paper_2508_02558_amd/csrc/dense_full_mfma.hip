@@ -139,9 +139,7 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
   }
   // PV product of the last tile
   __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.av[i >> 2][i & 3]), pb[i >> 2], acc[i & 3], 0, 0, 0);
+  pv_block(f, pb, acc);
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   if (row_valid) {
