@@ -201,6 +201,38 @@ def test_r_one_reproduces_dense_attention_and_zero_queries_pick_lowest_positions
     np.testing.assert_allclose(score2.cpu().numpy(), 1.0 / (n_pre + n_suf), rtol=1e-5)
 
 
+@pytest.mark.parametrize("prompt,gen,block_index,modes", [
+    (9000, 96, 0, {}),                                                            # 9 chunks of 1024, ragged
+    (12288, 64, 0, dict(pool_mode=B.SDLLM_AVG_POOL)),                              # exactly 12 chunks, avg pooling
+    (20000, 96, 1, dict(select_mode=B.SDLLM_JOINT, k_rounding=B.SDLLM_FLOOR)),     # joint ranking across the seam
+    (30000, 64, 0, dict(evict_scope=B.SDLLM_EVICT_PREFIX_ONLY)),                   # suffix kept whole
+])
+def test_select_long_segments(prompt, gen, block_index, modes):
+    # segments of more than 8192 candidates are ranked by the kernel that keeps its keys in LDS
+    _note(f"[case] long-segment select prompt={prompt} modes={modes}")
+    for pool_kernel in (1, 3, 5, 7):   # windows 1, 3 and 5 have compile-time paths, 7 takes the generic pooling
+        w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=2, n_kv_heads=2, prompt=prompt, gen=gen, pool_kernel=pool_kernel,
+                                                 retention=0.3)
+        inp = wl.make_block_inputs(w, 0, block_index, 2, device=DEV)
+        shape = U.shape_for(w, block_index, **modes)
+        gl = U.GpuLayer(shape, DEV)
+        q = inp["q"][1].contiguous()
+        idx_gpu, pooled, _ = gl.score_select(q, inp["k_full"])
+        idx_orc, pooled_orc, _ = U.oracle_score_select(shape, q, inp["k_full"])
+        for begin, length, k in U.ranked_segments(shape):
+            if k >= 0:   # pooled values are defined for ranked candidates only
+                np.testing.assert_allclose(pooled[:, :, begin:begin + length].cpu().double().numpy(),
+                                           pooled_orc[:, :, begin:begin + length], rtol=2e-5, atol=1e-12)
+        for g in range(w.n_kv_heads):
+            U.compare_index_rows(idx_gpu[0, g], idx_orc[0, g], pooled_orc[0, g], w.seq_len, inp["block_off"], w.block,
+                                 U.ranked_segments(shape))
+        # and once more without the optional pooled/score outputs (the keys then never leave the chip)
+        gl.idx.fill_(-1)
+        B.sdllm_score_select(shape, q, inp["k_full"], gl.idx, None, None, gl.ws)
+        torch.cuda.synchronize()
+        assert (gl.idx[:, :, :gl.k_total].cpu().numpy() == idx_gpu).all()
+
+
 def test_scores_match_oracle_values():
     _note("[case] score / pooled values")
     for name, kw in (("llada8b_layer", dict(n_q_heads=4, n_kv_heads=4, prompt=500, gen=128)),
