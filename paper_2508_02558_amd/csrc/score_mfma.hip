@@ -178,12 +178,17 @@ __global__ __launch_bounds__(512) void score_cols_mfma_kernel(const ScoreParams 
       const int hh = i >> 5, row = i & 31;
       const size_t head = (size_t)b * p.hq + g * G + hh;
       const float* src = p.part_ml + head * p.n_stat_part * 64;
-      float m_tot = -INFINITY;
-      for (int s = 0; s < p.n_stat_part; ++s) m_tot = fmaxf(m_tot, src[s * 64 + row]);
-      float l_tot = 0.f;
+      // merge the partial (max, sum) pairs of pass 1 in one sweep (there can be dozens per row and
+      // every load is a trip to L2: sixteen pairs are requested together, then folded in)
+      float m_tot = -INFINITY, l_tot = 0.f;
+#pragma unroll 16
       for (int s = 0; s < p.n_stat_part; ++s) {
         const float m_s = src[s * 64 + row];
-        if (m_s != -INFINITY) l_tot += src[s * 64 + 32 + row] * __builtin_amdgcn_exp2f(m_s - m_tot);
+        const float l_s = src[s * 64 + 32 + row];
+        const float m_new = fmaxf(m_tot, m_s);
+        if (m_new != -INFINITY)
+          l_tot = l_tot * __builtin_amdgcn_exp2f(m_tot - m_new) + l_s * __builtin_amdgcn_exp2f(m_s - m_new);
+        m_tot = m_new;
       }
       lds_ml[i] = make_float2(m_tot, 1.f / l_tot);
     }
