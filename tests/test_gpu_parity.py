@@ -306,6 +306,14 @@ def test_grouped_query_kernel_at_large_batch():
         del inp2, gl2
 
 
+def test_grouped_query_kernel_with_key_splits():
+    # few (batch, KV head) rows but long keys: the shared-tile kernel then splits every row's keys over
+    # many workgroups (ragged last split, fp32 partials, combine) in both the dense and the sparse step
+    w = wl.WORKLOADS["dream7b_gqa"].scaled(batch=2, prompt=20000, gen=64, retention=0.9)
+    assert w.batch * w.n_q_heads * ((18000 + 29) // 32 + 1) >= GQA_SHARED_KERNEL_WAVE_TILES
+    _run_block(w, n_steps=3)
+
+
 def test_block_step_replays_identically_from_a_hip_graph():
     # the library only enqueues kernels (no allocation, no memset, no host sync), so a block step can
     # be captured; every replay must reproduce the eager result, with eager work in between
