@@ -103,3 +103,18 @@ def test_dense_attn_full_size_sampled_rows():
         ref = orc.attention(wl.to_f64(q[0, h:h + 1]), wl.to_f64(k[0, h:h + 1]), wl.to_f64(v[0, h:h + 1]))
         U.assert_close(out[0, h:h + 1], ref, "bf16", f"head {h}")
     assert torch.isfinite(out.float()).all()
+
+
+def test_dense_attn_peaked_softmax():
+    # logits spread over several dozen, and for every query row a dominant key late in the sequence
+    print("[case] dense_attn peaked softmax", flush=True)
+    torch.manual_seed(21)
+    Bt, Hq, Hkv, L, d = 1, 4, 2, 520, 128
+    q = (4.0 * torch.randn(Bt, Hq, L, d, device=DEV)).bfloat16()
+    k = (4.0 * torch.randn(Bt, Hkv, L, d, device=DEV)).bfloat16()
+    v = torch.randn(Bt, Hkv, L, d, device=DEV).bfloat16()
+    k[:, :, 400] = (1.5 * q[:, ::2, 7].float()).bfloat16()
+    out = torch.zeros(Bt, Hq, L, d, device=DEV, dtype=torch.bfloat16)
+    B.sdllm_dense_attn(_shape(Bt, Hq, Hkv, d, L, B.SDLLM_BF16), q, k, v, out)
+    torch.cuda.synchronize()
+    U.assert_close(out, U.oracle_attention_batch(q, k, v), "bf16", "peaked")

@@ -424,3 +424,32 @@ def test_block_step_on_sequence_major_views():
     torch.cuda.synchronize()
     ref = U.oracle_attention_batch(q[2], torch.cat([k_cache[:, :, :k_total], kb], 2), torch.cat([v_cache[:, :, :k_total], vb], 2))
     U.assert_close(out, ref, "bf16", "sparse, strided")
+
+
+@pytest.mark.parametrize("Bt,Hq,Hkv,n_cached", [(1, 4, 4, 700), (2, 14, 2, 333), (160, 28, 4, 300)])
+def test_attention_with_peaked_softmax_and_late_maxima(Bt, Hq, Hkv, n_cached):
+    # logits with a spread of several dozen (softmax close to one-hot) and, per row, a dominant key
+    # planted in a late tile: the running softmax reference has to jump by far more than its slack
+    # after many tiles have been accumulated, in the per-head, the key-split and (last case) the
+    # shared-tile grouped-query kernel
+    _note(f"[case] peaked softmax B={Bt} Hq={Hq} Hkv={Hkv} n_cached={n_cached}")
+    torch.manual_seed(77 + n_cached)
+    b, d = 32, 128
+    shape = B.make_shape(batch=Bt, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, seq_len=4096, block_off=2048,
+                         block_len=b, dtype=B.SDLLM_BF16, cache_rows=n_cached)
+    q = (4.0 * torch.randn(Bt, Hq, b, d, device=DEV)).bfloat16()
+    kc = (4.0 * torch.randn(Bt, Hkv, n_cached, d, device=DEV)).bfloat16()
+    vc = torch.randn(Bt, Hkv, n_cached, d, device=DEV).bfloat16()
+    kb = (4.0 * torch.randn(Bt, Hkv, b, d, device=DEV)).bfloat16()
+    vb = torch.randn(Bt, Hkv, b, d, device=DEV).bfloat16()
+    # a key aligned with the first query head's row 0, three quarters of the way through the cache
+    G = Hq // Hkv
+    kc[:, :, (3 * n_cached) // 4] = (1.5 * q[:, ::G, 0].float()).bfloat16()
+    out = torch.zeros(Bt, Hq, b, d, device=DEV, dtype=torch.bfloat16)
+    ws = torch.empty(B.sdllm_workspace_bytes(shape, B.SDLLM_OP_SPARSE_ATTN, n_cached), dtype=torch.uint8, device=DEV)
+    B.sdllm_sparse_attn(shape, q, kc, vc, n_cached, kb, vb, out, ws)
+    torch.cuda.synchronize()
+    bs = [0, Bt - 1] if Bt > 2 else list(range(Bt))
+    ref = U.oracle_attention_batch(q[bs], torch.cat([kc[bs], kb[bs]], 2), torch.cat([vc[bs], vb[bs]], 2))
+    U.assert_close(out[bs], ref, "bf16", "peaked softmax")
+    assert torch.isfinite(out.float()).all()
