@@ -143,6 +143,16 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
     if (n_split < 1) n_split = 1;
     pl.tiles_per_split = (tiles + n_split - 1) / n_split;
     pl.waves = pl.tiles_per_split < kMaxWavesPerWg ? pl.tiles_per_split : kMaxWavesPerWg;
+    // One workgroup per head: fewer, longer-running waves measured faster than eight (smaller merge at
+    // the end, 40-48 KB instead of 64 KB of loads in flight per CU).  With more heads than CUs four
+    // waves let two workgroups share a CU, so one streams while the other merges and writes
+    // (B=16 LLaDA shape: 94 -> 89 us; B=8: 47.5 -> 46.3 us with five waves).  Not for grouped-query
+    // heads served one workgroup per head: they are short of arithmetic throughput, not of bandwidth,
+    // and lose with fewer waves (B=8 Dream shape: 22 -> 26 us).
+    if (n_split == 1 && s.n_q_heads == s.n_kv_heads) {
+      const int cap = heads > kNumCUs ? 4 : 5;
+      if (pl.waves > cap) pl.waves = cap;
+    }
     pl.n_split = (tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;   // no empty split
     if (pl.n_split > 1) {
       const size_t slots = (size_t)heads * pl.n_split;
