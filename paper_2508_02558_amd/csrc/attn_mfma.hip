@@ -76,7 +76,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   float mc_run = -INFINITY, lc_run = 0.f;   // the same over candidate keys only (STATS)
 
   // Shallow scheme: one staging register set, used alternately for the K and the V tile, so a wave
-  // keeps exactly one 8 KB tensor tile in flight (64 KB per CU with 8 waves).  Measured on MI355X, a
+  // keeps exactly one 8 KB tensor tile in flight (40-64 KB per CU with 5-8 waves).  Measured on MI355X, a
   // streaming read is fastest with 32-64 KB outstanding per CU and loses ~5 % at 128 KB, so K(t+1)
   // flies under the PV product of tile t and V(t) under its logits/softmax.
   u32x4 reg[8], reg2[DEEP ? 8 : 1];
