@@ -11,11 +11,11 @@
 //   * global loads are full-row coalesced (16 lanes x 16 B per 256-byte row), held in registers
 //     for one tile of look-ahead, then written to a wave-private, row-padded LDS tile from
 //     which the MFMA operand fragments are read without bank conflicts;
-//   * V is read from LDS as 8-byte pieces of four head-dim columns and regrouped with v_perm so
-//     that four MFMAs cover all 128 columns (lane m of MFMA e produces column 4m+e);
-//   * up to 8 waves per workgroup split the keys of one head and merge their running
-//     (max, sum, numerator) through LDS; more workgroups per head (split-KV) write fp32
-//     partials that a small combine kernel merges.
+//   * the V^T operands come straight out of the row-major V tile through the transposing LDS read
+//     (ds_read_b64_tr_b16), four MFMAs covering the 128 columns (MFMA e produces columns 32e + m);
+//   * up to 8 waves per workgroup (the planner picks 4 or 5 for unsplit MHA heads) split the keys of
+//     one head and merge their running (max, sum, numerator) through LDS; more workgroups per head
+//     (split-KV) write fp32 partials that a small combine kernel merges.
 #include "attn_tile_math.h"
 
 namespace sdllm {
