@@ -186,7 +186,7 @@ void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const size_t slot = (size_t)head * p.n_split + split;
-  write_wave_result(acc, m_run, l_tot, lane, half, col, p.n_split == 1,
+  write_wave_result(acc, m_run, l_tot, lane, half, p.n_split == 1,
                     (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr), p.part_o + (slot * 32 + col) * 128,
                     p.part_ml + slot * 64);
 }

@@ -158,7 +158,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
       p.cand_ml[slot * 64 + lane] = mc_run;
       p.cand_ml[slot * 64 + 32 + lane] = lc_tot;
     }
-    write_wave_result(acc, m_run, l_tot, lane, half, col, p.n_split == 1,
+    write_wave_result(acc, m_run, l_tot, lane, half, p.n_split == 1,
                       (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr), p.part_o + (slot * 32 + col) * 128,
                       p.part_ml + slot * 64);
     return;

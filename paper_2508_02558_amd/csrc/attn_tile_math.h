@@ -192,8 +192,7 @@ __device__ __forceinline__ int out_col0(int e, int i4, int half) { return 32 * e
 // One wave owns the complete result of a head (or of a key split of it): normalised bf16 rows to
 // `out_row` (n_split == 1) or fp32 numerators + (max, sum) to the split-KV partial buffers.
 __device__ __forceinline__ void write_wave_result(const f32x16 (&acc)[4], float m_run, float l_tot, int lane, int half,
-                                                  int col, bool final_out, char* out_row, float* part_o_row,
-                                                  float* part_ml_slot) {
+                                                  bool final_out, char* out_row, float* part_o_row, float* part_ml_slot) {
   if (final_out) {
     const float inv = 1.f / l_tot;
 #pragma unroll

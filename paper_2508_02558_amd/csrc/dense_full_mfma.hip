@@ -144,7 +144,7 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   if (row_valid) {
     char* out_row = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + (int64_t)q_row * p.o_sr);
-    write_wave_result(acc, m_run, l_tot, lane, half, col, true, out_row, nullptr, nullptr);
+    write_wave_result(acc, m_run, l_tot, lane, half, true, out_row, nullptr, nullptr);
   }
 }
 
