@@ -80,6 +80,12 @@ def test_dream_long_full_size():
     _full_block(wl.WORKLOADS["dream_long"], samples=[(0, 0), (0, 3)])
 
 
+def test_dream7b_gen512_full_size():
+    # the grouped-query bench workload: B=8, 28 query / 4 KV heads, prompt 4096, 512-token generation
+    # (dense step through the shared-tile kernel with key splits, sparse step one workgroup per head)
+    _full_block(wl.WORKLOADS["dream7b_gen512"], samples=[(0, 0), (7, 3), (4, 2)])
+
+
 def test_gen512_late_block_full_size():
     # 512-token generation after a 4k input: block 13 of 16 has a 4512-token prefix and a 64-token suffix
     w = wl.WORKLOADS["llada8b_gen512"].scaled(batch=2)
