@@ -182,7 +182,7 @@ int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, cons
   p.n_split = pl.n_split; p.tiles_per_split = pl.tiles_per_split; p.waves = pl.waves;
   p.part_o = (float*)ws;
   p.part_ml = (float*)((char*)ws + pl.part_o_bytes);
-  p.cand_ml = pl.mfma && !pl.gqa && p.group == 1 ? cand_ml : nullptr;
+  p.cand_ml = pl.mfma ? cand_ml : nullptr;
   p.cand0_end = cand0_end;
   p.cand1_begin = cand1_begin;
   hipError_t e;
@@ -312,7 +312,7 @@ BlockStepWs plan_block_step(const sdllm_shape_t& s) {
   if (sparse.ws_bytes() > w.base) w.base = sparse.ws_bytes();
   if (sc.ws_bytes() > w.base) w.base = sc.ws_bytes();
   w.base = align_up(w.base);
-  w.fuse = dense.mfma && !dense.gqa && s.n_q_heads == s.n_kv_heads && sc.mfma && s.score_mode == SDLLM_SOFTMAX_MEAN && c.n_cand > 0;
+  w.fuse = dense.mfma && sc.mfma && s.score_mode == SDLLM_SOFTMAX_MEAN && c.n_cand > 0;
   w.stats_parts = dense.n_split;
   w.stats_bytes = w.fuse ? align_up((size_t)s.batch * s.n_q_heads * dense.n_split * 64 * sizeof(float)) : 0;
   return w;

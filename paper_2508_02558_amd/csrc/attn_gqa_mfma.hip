@@ -16,6 +16,12 @@
 // so both land on the same XCD and the second read of a K/V line is an L2 hit.
 // Each wave owns its head's result, so there is no cross-wave merge; key splits write fp32 partials
 // for the combine kernel.
+// STATS (dense launches of the cache-update step): also leave each query row's softmax (max, sum)
+// over the CANDIDATE keys only, which is the row-statistics pass of the saliency scoring (Sec. 3.3,
+// Alg. 1 steps 2-6).  The tiles made of candidates alone are visited first, so up to there the
+// running attention statistics ARE the candidate statistics and a copy of them is all it takes; the
+// one or two tiles that also hold the block's own keys (with prefix-only eviction: the suffix too)
+// come last and add their candidates to that copy with a masked pass of their own.
 #include "attn_tile_math.h"
 
 namespace sdllm {
@@ -28,11 +34,12 @@ constexpr int gqa_chunks(int waves) { return (kTileChunks + waves * kWave - 1) /
 constexpr size_t gqa_lds_bytes(int waves) { return 2 * (size_t)gqa_stage_tiles(waves) * kKvTileBytes; }
 constexpr int gqa_head_splits(int group) { return group >= 4 ? 2 : 1; }
 
-// Stage `stage_idx` of this workgroup's tile range into registers, all threads together: piece
-// c = tid + i*T of a tile is 16-byte chunk c%16 of row c/16.  A tile never straddles the two key
+// Stage the tiles first_tile, ... of this workgroup's range (positions in its visiting order; tile_of
+// gives the tile in memory) into registers, all threads together: piece c = tid + i*T of a tile is
+// 16-byte chunk c%16 of row c/16.  A tile never straddles the two key
 // segments, so its base is workgroup-uniform and K and V share offsets.
-template <int W>
-__device__ __forceinline__ void gqa_load_stage(const SegPtrs& sp, int first_tile, int t_end, int tid,
+template <int W, class TileMap>
+__device__ __forceinline__ void gqa_load_stage(const SegPtrs& sp, int first_tile, int t_end, int tid, const TileMap& tile_of,
                                                u32x4 (&kreg)[gqa_stage_tiles(W) * gqa_chunks(W)],
                                                u32x4 (&vreg)[gqa_stage_tiles(W) * gqa_chunks(W)]) {
   constexpr int NT = gqa_stage_tiles(W), CH = gqa_chunks(W), T = W * kWave;
@@ -40,7 +47,7 @@ __device__ __forceinline__ void gqa_load_stage(const SegPtrs& sp, int first_tile
   for (int j = 0; j < NT; ++j) {
     if (first_tile + j >= t_end) break;      // workgroup-uniform
     uint32_t stride;
-    const TileSrc ts = tile_src(sp, first_tile + j, stride);
+    const TileSrc ts = tile_src(sp, tile_of(first_tile + j), stride);
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int c = tid + i * T;
@@ -71,8 +78,32 @@ __device__ __forceinline__ void gqa_store_stage(uint8_t* stage, int tid, const u
     }
 }
 
+// Adds the candidates among a tile's keys to a row's running candidate-only (max, sum): register i of
+// the raw logits is key position pos0 + 8*(i/4) + i%4; candidates are the positions before
+// cand0_end or from cand1_begin on, within the sequence.  The reference mc_run is common to the two
+// half-lanes of a row, the sum is per half-lane (like the attention's own pair).
+__device__ __forceinline__ void tile_candidate_stats(const f32x16& sn, int pos0, const AttnParams& p, float& mc_run, float& lc_run) {
+  float sc[16];
+  float mc_loc = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int pos = pos0 + (i >> 2) * 8 + (i & 3);
+    sc[i] = ((pos < p.cand0_end || pos >= p.cand1_begin) && pos < p.seg[0].n) ? sn[i] * p.scale_log2 : -INFINITY;
+    mc_loc = fmaxf(mc_loc, sc[i]);
+  }
+  mc_loc = fmaxf(mc_loc, __shfl_xor(mc_loc, 32));
+  const float mc_new = fmaxf(mc_run, mc_loc);
+  if (mc_new != -INFINITY) {
+    float lc_loc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) lc_loc += __builtin_amdgcn_exp2f(sc[i] - mc_new);
+    lc_run = lc_run * __builtin_amdgcn_exp2f(mc_run - mc_new) + lc_loc;
+    mc_run = mc_new;
+  }
+}
+
 // two waves per SIMD (256 registers each) whatever the workgroup size: a CU has to hold 8 of these waves
-template <int NSEG, int W>
+template <int NSEG, int W, bool STATS>
 __global__ __launch_bounds__(W * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
   constexpr int NT = gqa_stage_tiles(W);
@@ -114,6 +145,16 @@ void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
   const int nt = t_end - t_begin;            // >= 1: the planner leaves no split empty
   const int nstages = (nt + NT - 1) / NT;
 
+  // Visiting order (STATS; one key segment): tiles [x0, x0 + n_mixed) hold keys that are not
+  // candidates and are visited last, positions [n_pure, ntiles) of the order.
+  int x0 = 0, n_mixed = 0;
+  if (STATS) {
+    x0 = p.cand0_end / kTileKeys;
+    n_mixed = max(min(ntiles, (p.cand1_begin + kTileKeys - 1) / kTileKeys) - x0, 0);
+  }
+  const int n_pure = ntiles - n_mixed;
+  auto tile_of = [&](int t) { return !STATS || t < x0 ? t : (t < n_pure ? t + n_mixed : x0 + (t - n_pure)); };
+
   bf16x8 qf[8];
   load_q_frags((const char*)p.q + 2 * (b * p.q_sb + h * p.q_sh + col * p.q_sr), half, qf);
 
@@ -123,19 +164,20 @@ void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[e][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  float mc_run = -INFINITY, lc_run = 0.f;   // the same over candidate keys only (STATS)
 
   // valid keys of local tile j (only the last tile of a segment is ragged)
   auto rows_of = [&](int j) {
-    const int t = t_begin + j;
+    const int t = tile_of(t_begin + j);
     return t < sp.tiles0 ? min(kTileKeys, sp.n0 - t * kTileKeys) : min(kTileKeys, sp.n1 - (t - sp.tiles0) * kTileKeys);
   };
   // LDS address of local tile j: stage j / NT (double-buffered), slot j % NT
   auto tile_lds = [&](int j) { return smem + ((j / NT) & 1) * kStageBytes + (j % NT) * kKvTileBytes; };
 
   u32x4 kreg[NT * gqa_chunks(W)], vreg[NT * gqa_chunks(W)];
-  gqa_load_stage<W>(sp, t_begin, t_end, tid, kreg, vreg);
+  gqa_load_stage<W>(sp, t_begin, t_end, tid, tile_of, kreg, vreg);
   gqa_store_stage<W>(smem, tid, kreg, vreg);
-  if (nstages > 1) gqa_load_stage<W>(sp, t_begin + NT, t_end, tid, kreg, vreg);
+  if (nstages > 1) gqa_load_stage<W>(sp, t_begin + NT, t_end, tid, tile_of, kreg, vreg);
   __syncthreads();
 
   // Pipeline state between iterations: pb = softmax numerators of the current tile j (bf16), f = its V
@@ -154,11 +196,19 @@ void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
       const int s_new = (j + 2) / NT;
       gqa_store_stage<W>(smem + (s_new & 1) * kStageBytes, tid, kreg, vreg);
       __syncthreads();
-      if (s_new + 1 < nstages) gqa_load_stage<W>(sp, t_begin + (s_new + 1) * NT, t_end, tid, kreg, vreg);
+      if (s_new + 1 < nstages) gqa_load_stage<W>(sp, t_begin + (s_new + 1) * NT, t_end, tid, tile_of, kreg, vreg);
     }
     if (!head_valid) return;
     if (j + 2 < nt) tile_k_load(tile_lds(j + 2), half, col, a);
     __builtin_amdgcn_sched_barrier(0);
+    if (STATS) {
+      const int pos = t_begin + j + 1;   // of tile j+1 in the visiting order
+      if (pos >= n_pure) {
+        // first tile with other keys: what the attention has accumulated so far covers candidates only
+        if (pos == max(n_pure, t_begin)) { mc_run = m_run; lc_run = l_run; }
+        tile_candidate_stats(sn, tile_of(pos) * kTileKeys + half * 4, p, mc_run, lc_run);
+      }
+    }
     softmax_block(sn, rows_of(j + 1), p.scale_log2, half, m_run, l_run, acc, pb);
   };
 
@@ -186,28 +236,36 @@ void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const size_t slot = (size_t)head * p.n_split + split;
+  if (STATS) {
+    if (t_end <= n_pure) { mc_run = m_run; lc_run = l_run; }   // this split saw candidates only
+    const float lc_tot = lc_run + __shfl_xor(lc_run, 32);
+    if (lane < 32) {
+      p.cand_ml[slot * 64 + lane] = mc_run;
+      p.cand_ml[slot * 64 + 32 + lane] = lc_tot;
+    }
+  }
   write_wave_result(acc, m_run, l_tot, lane, half, p.n_split == 1,
                     (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr), p.part_o + (slot * 32 + col) * 128,
                     p.part_ml + slot * 64);
 }
 
-template <int NSEG, int W>
+template <int NSEG, int W, bool STATS>
 static hipError_t launch_w(const AttnParams& p, int head_splits, hipStream_t s) {
   static LdsOptIn lds;
-  const hipError_t e = lds.ensure(reinterpret_cast<const void*>(attn_gqa_mfma_bf16_kernel<NSEG, W>), (int)gqa_lds_bytes(W));
+  const hipError_t e = lds.ensure(reinterpret_cast<const void*>(attn_gqa_mfma_bf16_kernel<NSEG, W, STATS>), (int)gqa_lds_bytes(W));
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_gqa_mfma_bf16_kernel<NSEG, W>), dim3(p.n_split * p.batch * p.hkv * head_splits), dim3(W * kWave),
+  hipLaunchKernelGGL((attn_gqa_mfma_bf16_kernel<NSEG, W, STATS>), dim3(p.n_split * p.batch * p.hkv * head_splits), dim3(W * kWave),
                      gqa_lds_bytes(W), s, p, head_splits);
   return hipGetLastError();
 }
 
-template <int NSEG>
+template <int NSEG, bool STATS>
 static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
   const int hs = gqa_head_splits(p.group);
   switch ((p.group + hs - 1) / hs) {   // waves per workgroup
-    case 2: return launch_w<NSEG, 2>(p, hs, s);
-    case 3: return launch_w<NSEG, 3>(p, hs, s);
-    case 4: return launch_w<NSEG, 4>(p, hs, s);
+    case 2: return launch_w<NSEG, 2, STATS>(p, hs, s);
+    case 3: return launch_w<NSEG, 3, STATS>(p, hs, s);
+    case 4: return launch_w<NSEG, 4, STATS>(p, hs, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -215,14 +273,14 @@ static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
 bool attn_gqa_supports_group(int group) { return group >= 2 && group <= 8; }
 
 hipError_t launch_attn_gqa_mfma_bf16(const AttnParams& p, hipStream_t s) {
-  if (p.seg[0].n > 0 && p.seg[1].n > 0) return launch_nseg<2>(p, s);
+  if (p.seg[0].n > 0 && p.seg[1].n > 0) return launch_nseg<2, false>(p, s);
   if (p.seg[1].n > 0) {   // empty cache: the block is the only key tensor
     AttnParams q = p;
     q.seg[0] = p.seg[1];
     q.seg[1].n = 0;
-    return launch_nseg<1>(q, s);
+    return launch_nseg<1, false>(q, s);
   }
-  return launch_nseg<1>(p, s);
+  return p.cand_ml ? launch_nseg<1, true>(p, s) : launch_nseg<1, false>(p, s);
 }
 
 }  // namespace sdllm

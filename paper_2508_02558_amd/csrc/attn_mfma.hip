@@ -257,10 +257,7 @@ template <int NSEG, bool STATS>
 static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
   // at most half the CUs busy: latency-bound, take the deep prefetch
   const bool deep = p.batch * p.hq * p.n_split <= kNumCUs / 2;
-  if (p.group > 1) {
-    if (STATS) return hipErrorInvalidValue;   // fused statistics exist for group == 1 only
-    return deep ? launch_variant<NSEG, false, true, true>(p, s) : launch_variant<NSEG, false, false, true>(p, s);
-  }
+  if (p.group > 1) return deep ? launch_variant<NSEG, STATS, true, true>(p, s) : launch_variant<NSEG, STATS, false, true>(p, s);
   return deep ? launch_variant<NSEG, STATS, true, false>(p, s) : launch_variant<NSEG, STATS, false, false>(p, s);
 }
 

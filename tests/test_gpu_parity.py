@@ -259,6 +259,15 @@ def test_scores_match_oracle_values():
 GQA_SHARED_KERNEL_WAVE_TILES = 30000   # plan_attn (csrc/api.hip): heads x 32-key tiles from which the shared-tile kernel runs
 
 
+def _check_selected_rows(gl, shape, w, q, k_full, o, b, rows):
+    """Index sets of the batch elements `rows` after a cache-update step, against the oracle."""
+    idx_gpu = gl.idx[rows, :, :gl.k_total].cpu().numpy().astype(np.int64)
+    idx_orc, pooled_orc, _ = U.oracle_score_select(shape, q[rows], k_full[rows])
+    for i in range(len(rows)):
+        for g in range(w.n_kv_heads):
+            U.compare_index_rows(idx_gpu[i, g], idx_orc[i, g], pooled_orc[i, g], w.seq_len, o, b, U.ranked_segments(shape))
+
+
 def _batch_for_shared_kernel(n_q_heads, n_keys_sparse):
     tiles = -(-n_keys_sparse // 32) + 1            # cache tiles + the block's own tile
     return -(-GQA_SHARED_KERNEL_WAVE_TILES // (n_q_heads * tiles)) + 1
@@ -278,6 +287,7 @@ def test_grouped_query_kernel_at_large_batch():
     assert gl.block_step(1, 1, q1, inp["k_full"], inp["v_full"]) == 1
     bs = [0, 7, w.batch - 1]
     U.assert_close(gl.out[bs], U.oracle_attention_batch(q1[bs], inp["k_full"][bs], inp["v_full"][bs]), "bf16", "dense gqa")
+    _check_selected_rows(gl, shape, w, q1, inp["k_full"], o, b, bs)
     q2, kb, vb = inp["q"][2].contiguous(), inp["k_blk"][2].contiguous(), inp["v_blk"][2].contiguous()
     assert gl.block_step(2, 1, q2, kb, vb) == 2
     kt = gl.k_total
@@ -297,6 +307,7 @@ def test_grouped_query_kernel_at_large_batch():
         last = w2.batch - 1
         bs2 = [0, last]
         U.assert_close(gl2.out[bs2], U.oracle_attention_batch(q[bs2], inp2["k_full"][bs2], inp2["v_full"][bs2]), "bf16", f"dense G={G}")
+        _check_selected_rows(gl2, gl2.shape, w2, q, inp2["k_full"], inp2["block_off"], w2.block, bs2)
         q2, kb, vb = inp2["q"][2].contiguous(), inp2["k_blk"][2].contiguous(), inp2["v_blk"][2].contiguous()
         gl2.block_step(2, 1, q2, kb, vb)
         kt = gl2.k_total
@@ -306,12 +317,19 @@ def test_grouped_query_kernel_at_large_batch():
         del inp2, gl2
 
 
-def test_grouped_query_kernel_with_key_splits():
+@pytest.mark.parametrize("prompt,modes", [
+    (20000, {}),                                              # block on a tile boundary
+    (20011, {}),                                              # the block's keys share two tiles with candidates
+    (20011, {"evict_scope": B.SDLLM_EVICT_PREFIX_ONLY}),      # the suffix is not scored either
+])
+def test_grouped_query_kernel_with_key_splits(prompt, modes):
     # few (batch, KV head) rows but long keys: the shared-tile kernel then splits every row's keys over
-    # many workgroups (ragged last split, fp32 partials, combine) in both the dense and the sparse step
-    w = wl.WORKLOADS["dream7b_gqa"].scaled(batch=2, prompt=20000, gen=64, retention=0.9)
+    # many workgroups (ragged last split, fp32 partials, combine) in both the dense and the sparse step;
+    # at the cache-update step it also supplies the scoring pass's row statistics, so the index sets
+    # checked here depend on its candidate-only (max, sum) in every split
+    w = wl.WORKLOADS["dream7b_gqa"].scaled(batch=2, prompt=prompt, gen=64, retention=0.9)
     assert w.batch * w.n_q_heads * ((18000 + 29) // 32 + 1) >= GQA_SHARED_KERNEL_WAVE_TILES
-    _run_block(w, n_steps=3)
+    _run_block(w, n_steps=3, **modes)
 
 
 def test_block_step_replays_identically_from_a_hip_graph():
