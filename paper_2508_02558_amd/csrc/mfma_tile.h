@@ -35,9 +35,22 @@ __device__ __forceinline__ uint32_t tile_off(int row, int chunk) {
 // NT: non-temporal loads for data that is streamed once per launch (they keep the tiles from
 // displacing reusable lines in L2/MALL and measured ~12 % faster on MI355X); plain loads when sibling
 // workgroups re-read the same rows (query heads of one KV group served by separate workgroups).
+// A full tile (the common case, wave-uniform test) is addressed as base + j * (4 rows) (scalar) plus ONE
+// per-lane offset, so the eight loads cost the vector ALU one multiply and eight adds instead of
+// eight clamps, eight multiplies and eight adds (with two such calls per tile the address arithmetic
+// was half of the vector-ALU time of an attention tile).
 template <bool NT = true>
 __device__ __forceinline__ void load_rows(const char* base, int rows, uint32_t stride, int lane, u32x4 (&reg)[8]) {
   const uint32_t c16 = (lane & 15) << 4;
+  if (rows == kTileKeys) {
+    const uint32_t lane_off = (uint32_t)(lane >> 4) * stride + c16;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const u32x4* src = reinterpret_cast<const u32x4*>(base + (size_t)(j * 4) * stride + lane_off);
+      reg[j] = NT ? __builtin_nontemporal_load(src) : *src;
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     int r = j * 4 + (lane >> 4);
