@@ -235,8 +235,11 @@ def test_select_long_segments(prompt, gen, block_index, modes):
 
 def test_scores_match_oracle_values():
     _note("[case] score / pooled values")
-    for name, kw in (("llada8b_layer", dict(n_q_heads=4, n_kv_heads=4, prompt=500, gen=128)),
-                     ("dream7b_gqa", dict(prompt=700, gen=96)), ("tiny", {})):
+    # every group size has its own instantiation of the two scoring passes (the stand-alone entry
+    # point runs its own row-statistics pass; inside a block step the dense attention supplies them)
+    groups = [("llada8b_layer", dict(n_q_heads=2 * G, n_kv_heads=2, prompt=97 + 61 * G, gen=64)) for G in (2, 3, 4, 5, 6, 8)]
+    for name, kw in [("llada8b_layer", dict(n_q_heads=4, n_kv_heads=4, prompt=500, gen=128)),
+                     ("dream7b_gqa", dict(prompt=700, gen=96)), ("tiny", {})] + groups:
         w = wl.WORKLOADS[name].scaled(**kw)
         inp = wl.make_block_inputs(w, n_steps=2)
         for mode in (B.SDLLM_SOFTMAX_MEAN, B.SDLLM_LOGIT_MEAN):
