@@ -335,6 +335,32 @@ def test_grouped_query_kernel_with_key_splits(prompt, modes):
     _run_block(w, n_steps=3, **modes)
 
 
+def test_fused_row_statistics_ignore_dominant_block_keys():
+    # At the cache-update step the dense attention also supplies the scoring softmax's row statistics,
+    # which run over the candidates only.  Here every query's own block key dominates its attention
+    # row by about e^90 (k = 8 q): statistics taken relative to the attention's reference, or
+    # including the block's keys, would underflow to zero scores.  Multi-head, grouped-query per-head
+    # and grouped-query shared-tile kernels, block off the tile grid.
+    _note("[case] fused row statistics under dominant block keys")
+    base = wl.WORKLOADS["dream7b_gqa"].scaled(prompt=333, gen=64)
+    cases = [wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=4, n_kv_heads=4, prompt=300, gen=64), base,
+             base.scaled(batch=_batch_for_shared_kernel(base.n_q_heads, 333 + 64))]
+    for w in cases:
+        inp = wl.make_block_inputs(w, n_steps=2, device=DEV)
+        shape = U.shape_for(w)
+        gl = U.GpuLayer(shape, DEV)
+        o, b, G = inp["block_off"], w.block, w.group
+        k_full, v_full = inp["k_full"], inp["v_full"]
+        rows = sorted({0, w.batch - 1})
+        for t in range(2):
+            q = inp["q"][t].contiguous()
+            k_full[:, :, o:o + b] = 8 * q[:, ::G]          # exact in bf16 (power of two)
+            v_full[:, :, o:o + b] = inp["v_blk"][t]
+            assert gl.block_step(t, 1, q, k_full, v_full) == t
+            U.assert_close(gl.out[rows], U.oracle_attention_batch(q[rows], k_full[rows], v_full[rows]), w.dtype, f"dense step {t}")
+        _check_selected_rows(gl, shape, w, q, k_full, o, b, rows)
+
+
 def test_block_step_replays_identically_from_a_hip_graph():
     # the library only enqueues kernels (no allocation, no memset, no host sync), so a block step can
     # be captured; every replay must reproduce the eager result, with eager work in between
