@@ -116,7 +116,7 @@ void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
   const int col = lane & 31;
 
   // linear id -> (key split, batch * KV head, head split); the two head splits of a pair sit 8 ids
-  // apart (same XCD under round-robin dispatch) whenever the grid is a multiple of 16
+  // apart (same XCD under round-robin dispatch)
   const int lid = blockIdx.x;
   int pair = lid, hs = 0;
   if (head_splits == 2) {
@@ -124,8 +124,10 @@ void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
       hs = (lid >> 3) & 1;
       pair = ((lid >> 4) << 3) | (lid & 7);
     } else {
-      hs = lid & 1;
-      pair = lid >> 1;
+      // any other grid: neighbours in the XCD-contiguous numbering (dealt ids 8 apart, same XCD)
+      const int cid = xcd_contiguous_id(lid, gridDim.x);
+      hs = cid & 1;
+      pair = cid >> 1;
     }
   }
   const int split = pair % p.n_split;

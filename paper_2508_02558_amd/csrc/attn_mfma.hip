@@ -45,9 +45,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
 
   // Consecutive workgroup ids go round-robin over the 8 XCDs; renumber so that the workgroups of
   // one KV group (its query heads and key splits) sit on one XCD and share that XCD's L2.
-  int wg = blockIdx.x;
-  const int nwg = gridDim.x;
-  if ((nwg & (kNumXCDs - 1)) == 0) wg = (wg & (kNumXCDs - 1)) * (nwg / kNumXCDs) + wg / kNumXCDs;
+  const int wg = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int split = wg % p.n_split;
   const int head = wg / p.n_split;
   const int b = head / p.hq;

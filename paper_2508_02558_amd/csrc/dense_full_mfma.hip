@@ -61,9 +61,7 @@ __global__ __launch_bounds__(512) void dense_full_mfma_bf16_kernel(const DenseFu
 
   // renumber workgroups so that consecutive ids (which go round-robin over the XCDs) of one head's
   // query blocks end up on the same XCD
-  int wg = blockIdx.x;
-  const int nwg = gridDim.x;
-  if ((nwg & (kNumXCDs - 1)) == 0) wg = (wg & (kNumXCDs - 1)) * (nwg / kNumXCDs) + wg / kNumXCDs;
+  const int wg = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int qblocks = (p.seq_len + kFullRowsPerWg - 1) / kFullRowsPerWg;
   const int qb = wg % qblocks;
   const int head = wg / qblocks;

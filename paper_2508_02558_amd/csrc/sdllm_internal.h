@@ -16,6 +16,15 @@ constexpr int kMaxWavesPerWg = 8;    // attention / scoring workgroups hold up t
 constexpr int kNumCUs = 256;         // MI355X
 constexpr int kNumXCDs = 8;
 
+// Workgroup ids are dealt round-robin over the 8 XCDs, each with its own L2.  This renumbering gives
+// every XCD one contiguous range of the result instead (XCD x gets the ids it was dealt, in order,
+// placed after those of the XCDs before it), for any grid size, so that neighbours in the new
+// numbering - the query heads of a KV group, the key splits of a head - share an L2.
+__host__ __device__ inline int xcd_contiguous_id(int dealt, int n) {
+  const int x = dealt % kNumXCDs, q = n / kNumXCDs, r = n % kNumXCDs;
+  return x * q + (x < r ? x : r) + dealt / kNumXCDs;
+}
+
 // Kernels that need more than the default 64 KB of dynamic LDS have to opt in, once per device (the
 // attribute belongs to the device's copy of the kernel).  One object per kernel remembers which
 // devices are done; concurrent host threads at worst both set the same value.
