@@ -108,14 +108,18 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   // Grouped-query heads: either one workgroup per query head (K/V then come G times out of L2, but the
   // eight waves of a head split its keys and merge in LDS) or the shared-tile kernel (K/V read once,
   // one wave per head, key splits merged through fp32 partials and a second launch).  Measured on
-  // MI355X (G = 7, 4, 2; batch 1-32; 2k-33k keys, sparse and dense steps) the shared-tile kernel wins
-  // once there are about 30 000 wave-tiles of work (heads x 32-key tiles), and from about half of
-  // that when each head has 512 tiles or more (long prompts: 74 -> 49 us for the dense step of the
-  // batch-1 32k-prompt Dream shape).
+  // MI355X (G = 2, 3, 4, 5, 7, 8; batch 1-64; 2k-49k keys; sparse and dense steps), in wave-tiles of
+  // work (heads x 32-key tiles): with four waves per workgroup (G = 7, 8) the shared-tile kernel wins
+  // from about 30 000, and from about 22 000 when each head has 512 tiles or more (long prompts: the
+  // dense step of the batch-1 32k-prompt Dream shape 48.6 -> 44.4 us, of the 48k one 65 -> 56 us);
+  // with two waves per workgroup (G = 2, 4) only from about 70 000 (G = 2, 1024 heads x 69 tiles:
+  // 125 -> 90 us, but 512 heads x 136 tiles: 114 against 125 us).
   const int all_tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
   const int64_t wave_tiles = (int64_t)s.batch * s.n_q_heads * all_tiles;
-  pl.gqa = pl.mfma && attn_gqa_supports_group(s.n_q_heads / s.n_kv_heads) &&
-           (wave_tiles >= 30000 || (all_tiles >= 512 && wave_tiles >= 14000));
+  const int group = s.n_q_heads / s.n_kv_heads;
+  pl.gqa = pl.mfma && attn_gqa_supports_group(group) &&
+           (attn_gqa_waves_per_wg(group) >= 4 ? wave_tiles >= 30000 || (all_tiles >= 512 && wave_tiles >= 22000)
+                                              : wave_tiles >= 70000);
   if (pl.gqa) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int rows = s.batch * s.n_kv_heads;

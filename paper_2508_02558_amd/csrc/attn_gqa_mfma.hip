@@ -1,5 +1,5 @@
 // Grouped-query variant of the bf16 MFMA block attention (Alg. 3, cache_state == 2, and the dense
-// block rows of states 0/1) for models whose G query heads share one KV head (2 <= G <= 8).
+// block rows of states 0/1) for models whose G query heads share one KV head (G = 2, 4, 7 or 8).
 //
 // A workgroup serves one (batch, KV head), a range of key tiles and W of the group's query heads
 // (wave w = one head).  The K/V tiles are loaded ONCE per workgroup, cooperatively and fully coalesced,
@@ -9,7 +9,7 @@
 // each wave runs the software pipeline of the full-sequence kernel: one block of sixteen MFMAs (logits
 // of tile j+1 interleaved with the PV product of tile j), the LDS fragment requests for the next
 // block, then the softmax of tile j+1.
-// Groups of 4 to 8 heads are served by TWO workgroups of ceil(G/2) waves that stream the same keys:
+// Groups of 4, 7 and 8 heads are served by TWO workgroups of ceil(G/2) waves that stream the same keys:
 // a CU holds 8 such waves either way, but two workgroups keep two stages of global loads in flight
 // and one's load latency hides under the other's arithmetic (one 7- or 8-wave workgroup per CU spent
 // a third of its time waiting for its single stage).  The pair is given linear workgroup ids 8 apart,
@@ -266,13 +266,20 @@ static hipError_t launch_nseg(const AttnParams& p, hipStream_t s) {
   const int hs = gqa_head_splits(p.group);
   switch ((p.group + hs - 1) / hs) {   // waves per workgroup
     case 2: return launch_w<NSEG, 2, STATS>(p, hs, s);
-    case 3: return launch_w<NSEG, 3, STATS>(p, hs, s);
     case 4: return launch_w<NSEG, 4, STATS>(p, hs, s);
     default: return hipErrorInvalidValue;
   }
 }
 
-bool attn_gqa_supports_group(int group) { return group >= 2 && group <= 8; }
+// Workgroups of two or four waves.  The three-wave shapes (G = 3, 5, 6: uneven staging pieces, one
+// tile per LDS stage) lost to the one-workgroup-per-head kernel at every size measured (G = 3, batch
+// 32, 2208 keys: 137 against 85 us) and are not instantiated.
+bool attn_gqa_supports_group(int group) { return group == 2 || group == 4 || group == 7 || group == 8; }
+
+int attn_gqa_waves_per_wg(int group) {
+  const int hs = gqa_head_splits(group);
+  return (group + hs - 1) / hs;
+}
 
 hipError_t launch_attn_gqa_mfma_bf16(const AttnParams& p, hipStream_t s) {
   if (p.seg[0].n > 0 && p.seg[1].n > 0) return launch_nseg<2, false>(p, s);

@@ -147,6 +147,7 @@ struct DenseFullParams {
 hipError_t launch_attn_mfma_bf16(const AttnParams& p, hipStream_t s);
 hipError_t launch_attn_gqa_mfma_bf16(const AttnParams& p, hipStream_t s);
 bool attn_gqa_supports_group(int group);
+int attn_gqa_waves_per_wg(int group);
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_attn_combine(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_score_mfma_bf16(const ScoreParams& p, hipStream_t s);

@@ -259,7 +259,10 @@ def test_scores_match_oracle_values():
                 np.testing.assert_allclose(pg, pooled_orc, rtol=0, atol=2e-5)
 
 
-GQA_SHARED_KERNEL_WAVE_TILES = 30000   # plan_attn (csrc/api.hip): heads x 32-key tiles from which the shared-tile kernel runs
+def _shared_kernel_wave_tiles(group):
+    """plan_attn (csrc/api.hip): heads x 32-key tiles from which the shared-tile grouped-query kernel runs
+    (groups of 3, 5 and 6 heads always take the one-workgroup-per-head kernel)."""
+    return {7: 30000, 8: 30000, 2: 70000, 4: 70000}[group]
 
 
 def _check_selected_rows(gl, shape, w, q, k_full, o, b, rows):
@@ -271,9 +274,9 @@ def _check_selected_rows(gl, shape, w, q, k_full, o, b, rows):
             U.compare_index_rows(idx_gpu[i, g], idx_orc[i, g], pooled_orc[i, g], w.seq_len, o, b, U.ranked_segments(shape))
 
 
-def _batch_for_shared_kernel(n_q_heads, n_keys_sparse):
+def _batch_for_shared_kernel(n_q_heads, n_keys_sparse, group=7):
     tiles = -(-n_keys_sparse // 32) + 1            # cache tiles + the block's own tile
-    return -(-GQA_SHARED_KERNEL_WAVE_TILES // (n_q_heads * tiles)) + 1
+    return -(-_shared_kernel_wave_tiles(group) // (n_q_heads * tiles)) + 1
 
 
 def test_grouped_query_kernel_at_large_batch():
@@ -298,11 +301,13 @@ def test_grouped_query_kernel_at_large_batch():
                                    torch.cat([gl.v_cache[bs, :, :kt], vb[bs]], 2))
     U.assert_close(gl.out[bs], ref, "bf16", "sparse gqa")
     del inp, gl
-    # every group size has its own workgroup shape (waves, pieces per thread, tiles per LDS stage, one
-    # or two head splits); prompts chosen so that tile counts are odd and even, with ragged last tiles
-    for G, Hkv, prompt in ((2, 3, 70), (3, 2, 33), (4, 2, 130), (5, 1, 100), (6, 1, 257), (7, 1, 64), (8, 1, 70)):
+    # every group size the shared-tile kernel serves has its own workgroup shape (waves, pieces per
+    # thread, tiles per LDS stage, one or two head splits); prompts chosen so that tile counts are odd
+    # and even, with ragged last tiles.  Groups of 3, 5 and 6 heads run the one-workgroup-per-head
+    # kernel at any size; they go through the same checks at a batch of that order.
+    for G, Hkv, prompt in ((2, 3, 1000), (3, 2, 33), (4, 2, 905), (5, 1, 100), (6, 1, 257), (7, 1, 64), (8, 1, 70)):
         w2 = w.scaled(n_q_heads=G * Hkv, n_kv_heads=Hkv, prompt=prompt, gen=64)
-        w2 = w2.scaled(batch=_batch_for_shared_kernel(G * Hkv, -(-prompt // 2) + 16))
+        w2 = w2.scaled(batch=_batch_for_shared_kernel(G * Hkv, -(-prompt // 2) + 16, G if G in (2, 4, 7, 8) else 7))
         inp2 = wl.make_block_inputs(w2, n_steps=3, device=DEV)
         gl2 = U.GpuLayer(U.shape_for(w2), DEV)
         q = inp2["q"][1].contiguous()
@@ -331,7 +336,7 @@ def test_grouped_query_kernel_with_key_splits(prompt, modes):
     # at the cache-update step it also supplies the scoring pass's row statistics, so the index sets
     # checked here depend on its candidate-only (max, sum) in every split
     w = wl.WORKLOADS["dream7b_gqa"].scaled(batch=2, prompt=prompt, gen=64, retention=0.9)
-    assert w.batch * w.n_q_heads * ((18000 + 29) // 32 + 1) >= GQA_SHARED_KERNEL_WAVE_TILES
+    assert w.batch * w.n_q_heads * ((18000 + 29) // 32 + 1) >= _shared_kernel_wave_tiles(w.group)
     _run_block(w, n_steps=3, **modes)
 
 
@@ -344,7 +349,7 @@ def test_fused_row_statistics_ignore_dominant_block_keys():
     _note("[case] fused row statistics under dominant block keys")
     base = wl.WORKLOADS["dream7b_gqa"].scaled(prompt=333, gen=64)
     cases = [wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=4, n_kv_heads=4, prompt=300, gen=64), base,
-             base.scaled(batch=_batch_for_shared_kernel(base.n_q_heads, 333 + 64))]
+             base.scaled(batch=_batch_for_shared_kernel(base.n_q_heads, 333 + 64 - 32))]   # dense step: 13 tiles
     for w in cases:
         inp = wl.make_block_inputs(w, n_steps=2, device=DEV)
         shape = U.shape_for(w)
