@@ -138,14 +138,18 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   } else if (pl.mfma) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int heads = s.batch * s.n_q_heads;
-    // Split the keys of a head over workgroups only while the grid is small: about 192 workgroups
-    // in total and at least eleven tiles per workgroup were the fastest plans measured on MI355X.  A
-    // split costs fp32 partials and a second launch of about 4 us, which 21 tiles (672 keys) do not
-    // repay; beyond that batch-1 shapes are pure latency and a wave with one or two tiles beats a
-    // longer chain (1280 keys x 32 heads, dense step: 16.2 -> 13.3 us with 3 splits instead of 2;
-    // 28/4 heads x 4352 keys: 17.2 -> 15.0 us with 6 or 7 instead of 4).  From 192 heads on there is
-    // one workgroup per head.
-    int n_split = (192 + heads / 2) / heads;
+    // Split the keys of a head over workgroups only while the grid is small: as many splits as keep
+    // the grid within one workgroup per CU (an eight-wave workgroup fills a CU's LDS, so workgroup
+    // number 257 waits for a whole round: 56 heads x 4 splits 15.1 us, x 5 splits 22.3 us), at most 6
+    // (8 from 256 tiles per head on: 28 heads x 261 tiles, 20.4 us with 6 splits, 19.0 us with 8),
+    // and at least eleven tiles per workgroup.  A split costs fp32 partials and a second launch of
+    // about 4 us, which 21 tiles (672 keys) do not repay; beyond that batch-1 shapes are pure
+    // latency and a wave with one or two tiles beats a longer chain (1280 keys x 32 heads, dense
+    // step: 16.2 -> 14.8 us with 3 splits instead of 2; 28/4 heads x 4352 keys: 17.2 -> 15.0 us with
+    // 6 or 7 instead of 4).  From 129 heads on there is one workgroup per head.
+    int n_split = kNumCUs / heads;
+    const int most = tiles >= 256 ? 8 : 6;
+    if (n_split > most) n_split = most;
     const int max_split = tiles / 11;
     if (n_split > max_split) n_split = max_split;
     if (n_split < 1) n_split = 1;
