@@ -112,14 +112,15 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   // work (heads x 32-key tiles): with four waves per workgroup (G = 7, 8) the shared-tile kernel wins
   // from about 30 000, and from about 22 000 when each head has 512 tiles or more (long prompts: the
   // dense step of the batch-1 32k-prompt Dream shape 48.6 -> 44.4 us, of the 48k one 65 -> 56 us);
-  // with two waves per workgroup (G = 2, 4) only from about 70 000 (G = 2, 1024 heads x 69 tiles:
-  // 125 -> 90 us, but 512 heads x 136 tiles: 114 against 125 us).
+  // with two waves per workgroup (G = 2, 4) what decides is the number of heads, sparse and dense
+  // step alike: 512 heads lose (G = 4: 50/94 us per head against 55/97 us shared), 768 heads win
+  // (G = 4: 82/145 against 66/139 us; G = 2: 103/191 against 80/152 us).
   const int all_tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
   const int64_t wave_tiles = (int64_t)s.batch * s.n_q_heads * all_tiles;
   const int group = s.n_q_heads / s.n_kv_heads;
   pl.gqa = pl.mfma && attn_gqa_supports_group(group) &&
            (attn_gqa_waves_per_wg(group) >= 4 ? wave_tiles >= 30000 || (all_tiles >= 512 && wave_tiles >= 22000)
-                                              : wave_tiles >= 70000);
+                                              : s.batch * s.n_q_heads >= 640 && wave_tiles >= 40000);
   if (pl.gqa) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int rows = s.batch * s.n_kv_heads;
@@ -157,12 +158,14 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
     pl.waves = pl.tiles_per_split < kMaxWavesPerWg ? pl.tiles_per_split : kMaxWavesPerWg;
     // One workgroup per head: fewer, longer-running waves measured faster than eight (smaller merge at
     // the end, 40-48 KB instead of 64 KB of loads in flight per CU).  With more heads than CUs four
-    // waves let two workgroups share a CU, so one streams while the other merges and writes
-    // (B=16 LLaDA shape: 94 -> 89 us; B=8: 47.5 -> 46.3 us with five waves).  Not for grouped-query
-    // heads served one workgroup per head: they are short of arithmetic throughput, not of bandwidth,
-    // and lose with fewer waves (B=8 Dream shape: 22 -> 26 us).
-    if (n_split == 1 && s.n_q_heads == s.n_kv_heads) {
-      const int cap = heads > kNumCUs ? 4 : 5;
+    // waves let two workgroups share a CU, so one streams while the other merges and writes, and no
+    // workgroup waits for a second round (B=16 LLaDA shape: 94 -> 89 us; B=8: 47.5 -> 46.3 us with
+    // five waves; 280 grouped-query heads, G = 7: 41.4 -> 36.0 us; 320 heads, G = 4: 48.6 -> 43.6 us).
+    // Up to one head per CU the grouped-query heads keep eight waves: there they are short of
+    // arithmetic throughput, not of bandwidth (B=8 Dream shape: 22 -> 26 us with fewer).
+    if (n_split == 1) {
+      const bool mha = s.n_q_heads == s.n_kv_heads;
+      const int cap = heads > kNumCUs ? 4 : (mha ? 5 : kMaxWavesPerWg);
       if (pl.waves > cap) pl.waves = cap;
     }
     pl.n_split = (tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;   // no empty split

@@ -261,8 +261,12 @@ def test_scores_match_oracle_values():
 
 def _shared_kernel_wave_tiles(group):
     """plan_attn (csrc/api.hip): heads x 32-key tiles from which the shared-tile grouped-query kernel runs
-    (groups of 3, 5 and 6 heads always take the one-workgroup-per-head kernel)."""
-    return {7: 30000, 8: 30000, 2: 70000, 4: 70000}[group]
+    (groups of 3, 5 and 6 heads always take the one-workgroup-per-head kernel; groups of 2 and 4
+    also need SHARED_KERNEL_MIN_HEADS query heads in the batch)."""
+    return {7: 30000, 8: 30000, 2: 40000, 4: 40000}[group]
+
+
+SHARED_KERNEL_MIN_HEADS = 640   # two-wave workgroups (groups of 2 and 4 heads) only
 
 
 def _check_selected_rows(gl, shape, w, q, k_full, o, b, rows):
@@ -276,7 +280,10 @@ def _check_selected_rows(gl, shape, w, q, k_full, o, b, rows):
 
 def _batch_for_shared_kernel(n_q_heads, n_keys_sparse, group=7):
     tiles = -(-n_keys_sparse // 32) + 1            # cache tiles + the block's own tile
-    return -(-_shared_kernel_wave_tiles(group) // (n_q_heads * tiles)) + 1
+    batch = -(-_shared_kernel_wave_tiles(group) // (n_q_heads * tiles)) + 1
+    if group in (2, 4):
+        batch = max(batch, -(-SHARED_KERNEL_MIN_HEADS // n_q_heads))
+    return batch
 
 
 def test_grouped_query_kernel_at_large_batch():
