@@ -124,8 +124,10 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   if (pl.gqa) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int rows = s.batch * s.n_kv_heads;
-    // one workgroup per CU if the keys allow it, but never fewer than 4 tiles (two LDS stages) each
-    int n_split = (kNumCUs + rows - 1) / rows;
+    // as many key splits as keep the grid within the CUs' capacity (one workgroup per CU and head
+    // split: a few workgroups more would wait for a whole round), but never fewer than 4 tiles (two
+    // LDS stages) each
+    int n_split = rows < kNumCUs ? kNumCUs / rows : 1;
     const int max_split = tiles / 4 > 1 ? tiles / 4 : 1;
     if (n_split > max_split) n_split = max_split;
     pl.tiles_per_split = (tiles + n_split - 1) / n_split;
@@ -240,7 +242,10 @@ ScorePlan plan_score(const sdllm_shape_t& s) {
     if (waves_per_row > tiles) waves_per_row = tiles;
     if (waves_per_row < 1) waves_per_row = 1;
     pl.waves = waves_per_row < kMaxWavesPerWg ? waves_per_row : kMaxWavesPerWg;
-    const int n_part = (waves_per_row + pl.waves - 1) / pl.waves;
+    int n_part = (waves_per_row + pl.waves - 1) / pl.waves;
+    // never a few workgroups more than there are CUs: with several heads' Q staged in LDS a CU holds
+    // one scoring workgroup, and the extra ones would wait for a whole round
+    if (rows < (size_t)kNumCUs && n_part > kNumCUs / (int)rows) n_part = kNumCUs / (int)rows;
     pl.tiles_per_part = (tiles + n_part - 1) / n_part;
     pl.n_part = (tiles + pl.tiles_per_part - 1) / pl.tiles_per_part;   // no empty part
   }
