@@ -110,17 +110,21 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   // one wave per head, key splits merged through fp32 partials and a second launch).  Measured on
   // MI355X (G = 2, 3, 4, 5, 7, 8; batch 1-64; 2k-49k keys; sparse and dense steps), in wave-tiles of
   // work (heads x 32-key tiles): with four waves per workgroup (G = 7, 8) the shared-tile kernel wins
-  // from about 30 000, and from about 22 000 when each head has 512 tiles or more (long prompts: the
-  // dense step of the batch-1 32k-prompt Dream shape 48.6 -> 44.4 us, of the 48k one 65 -> 56 us);
+  // from about 30 000, from about 22 000 when each head has 512 tiles or more (long prompts: the
+  // dense step of the batch-1 32k-prompt Dream shape 48.6 -> 44.4 us, of the 48k one 65 -> 56 us),
+  // and from about 18 000 with 128 heads or more, whose rows need few key splits (140 heads x 136
+  // tiles: 37.9 -> 33.4 us; 84 heads x 264 tiles lose, 34.2 against 39.1 us);
   // with two waves per workgroup (G = 2, 4) what decides is the number of heads, sparse and dense
   // step alike: 512 heads lose (G = 4: 50/94 us per head against 55/97 us shared), 768 heads win
   // (G = 4: 82/145 against 66/139 us; G = 2: 103/191 against 80/152 us).
   const int all_tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
   const int64_t wave_tiles = (int64_t)s.batch * s.n_q_heads * all_tiles;
   const int group = s.n_q_heads / s.n_kv_heads;
+  const int heads_all = s.batch * s.n_q_heads;
   pl.gqa = pl.mfma && attn_gqa_supports_group(group) &&
-           (attn_gqa_waves_per_wg(group) >= 4 ? wave_tiles >= 30000 || (all_tiles >= 512 && wave_tiles >= 22000)
-                                              : s.batch * s.n_q_heads >= 640 && wave_tiles >= 40000);
+           (attn_gqa_waves_per_wg(group) >= 4
+                ? wave_tiles >= 30000 || (all_tiles >= 512 && wave_tiles >= 22000) || (heads_all >= 128 && wave_tiles >= 18000)
+                : heads_all >= 640 && wave_tiles >= 40000);
   if (pl.gqa) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int rows = s.batch * s.n_kv_heads;
