@@ -167,11 +167,13 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
     // waves let two workgroups share a CU, so one streams while the other merges and writes, and no
     // workgroup waits for a second round (B=16 LLaDA shape: 94 -> 89 us; B=8: 47.5 -> 46.3 us with
     // five waves; 280 grouped-query heads, G = 7: 41.4 -> 36.0 us; 320 heads, G = 4: 48.6 -> 43.6 us).
+    // With more than two heads per CU, two waves, so that four workgroups fit (544 heads, MHA:
+    // 117.9 -> 106.0 us; 640 heads: 134.5 -> 113.8 us; 768 heads of G = 3: 88.8 -> 75.0 us).
     // Up to one head per CU the grouped-query heads keep eight waves: there they are short of
     // arithmetic throughput, not of bandwidth (B=8 Dream shape: 22 -> 26 us with fewer).
     if (n_split == 1) {
       const bool mha = s.n_q_heads == s.n_kv_heads;
-      const int cap = heads > kNumCUs ? 4 : (mha ? 5 : kMaxWavesPerWg);
+      const int cap = heads > 2 * kNumCUs ? 2 : heads > kNumCUs ? 4 : (mha ? 5 : kMaxWavesPerWg);
       if (pl.waves > cap) pl.waves = cap;
     }
     pl.n_split = (tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;   // no empty split
