@@ -128,10 +128,15 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   if (pl.gqa) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int rows = s.batch * s.n_kv_heads;
-    // as many key splits as keep the grid within the CUs' capacity (one workgroup per CU and head
-    // split: a few workgroups more would wait for a whole round), but never fewer than 4 tiles (two
-    // LDS stages) each
-    int n_split = rows < kNumCUs ? kNumCUs / rows : 1;
+    // As many key splits as keep the grid within what the CUs hold at once (a few workgroups more
+    // would wait for a whole round), but never fewer than 4 tiles (two LDS stages) each.  Four-wave
+    // workgroups: two per CU.  Two-wave workgroups: four fit, three per CU measured best (G = 4,
+    // 768 heads: 79.6 -> 63.9 us with 2 splits; G = 2, 1024 heads: 90 us with 1 split, 108 with 2).
+    const int wg_waves = attn_gqa_waves_per_wg(group);
+    const int wgs_per_row = (group + wg_waves - 1) / wg_waves;   // head splits
+    const int room = (wg_waves >= 4 ? 2 : 3) * kNumCUs;
+    int n_split = room / (rows * wgs_per_row);
+    if (n_split < 1) n_split = 1;
     const int max_split = tiles / 4 > 1 ? tiles / 4 : 1;
     if (n_split > max_split) n_split = max_split;
     pl.tiles_per_split = (tiles + n_split - 1) / n_split;
