@@ -115,8 +115,8 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   // and from about 18 000 with 128 heads or more, whose rows need few key splits (140 heads x 136
   // tiles: 37.9 -> 33.4 us; 84 heads x 264 tiles lose, 34.2 against 39.1 us);
   // with two waves per workgroup (G = 2, 4) what decides is the number of heads, sparse and dense
-  // step alike: 512 heads lose (G = 4: 50/94 us per head against 55/97 us shared), 768 heads win
-  // (G = 4: 82/145 against 66/139 us; G = 2: 103/191 against 80/152 us).
+  // step alike: 256 heads lose (G = 4: 28/51 us per head against 34/50 us shared), 384 heads win
+  // (G = 4: 46/82 against 42/68 us; G = 2: 54/97 against 50/80 us), 512 heads tie, 640 win.
   const int all_tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
   const int64_t wave_tiles = (int64_t)s.batch * s.n_q_heads * all_tiles;
   const int group = s.n_q_heads / s.n_kv_heads;
@@ -124,7 +124,7 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   pl.gqa = pl.mfma && attn_gqa_supports_group(group) &&
            (attn_gqa_waves_per_wg(group) >= 4
                 ? wave_tiles >= 30000 || (all_tiles >= 512 && wave_tiles >= 22000) || (heads_all >= 128 && wave_tiles >= 18000)
-                : heads_all >= 640 && wave_tiles >= 40000);
+                : heads_all >= 320 && wave_tiles >= 26000);
   if (pl.gqa) {
     const int tiles = (n0 + kTileKeys - 1) / kTileKeys + (n1 + kTileKeys - 1) / kTileKeys;
     const int rows = s.batch * s.n_kv_heads;

@@ -263,10 +263,10 @@ def _shared_kernel_wave_tiles(group):
     """plan_attn (csrc/api.hip): heads x 32-key tiles from which the shared-tile grouped-query kernel runs
     (groups of 3, 5 and 6 heads always take the one-workgroup-per-head kernel; groups of 2 and 4
     also need SHARED_KERNEL_MIN_HEADS query heads in the batch)."""
-    return {7: 30000, 8: 30000, 2: 40000, 4: 40000}[group]
+    return {7: 30000, 8: 30000, 2: 26000, 4: 26000}[group]
 
 
-SHARED_KERNEL_MIN_HEADS = 640   # two-wave workgroups (groups of 2 and 4 heads) only
+SHARED_KERNEL_MIN_HEADS = 320   # two-wave workgroups (groups of 2 and 4 heads) only
 
 
 def _check_selected_rows(gl, shape, w, q, k_full, o, b, rows):
