@@ -347,6 +347,19 @@ def test_grouped_query_kernel_with_key_splits(prompt, modes):
     _run_block(w, n_steps=3, **modes)
 
 
+@pytest.mark.parametrize("heads,kv_heads,batch", [
+    (8, 8, 40),    # 320 heads: four-wave workgroups, two per CU
+    (8, 8, 70),    # 560 heads: two-wave workgroups, four per CU
+    (6, 2, 60),    # 360 grouped-query heads (G = 3, always one workgroup per head): four waves
+    (6, 2, 100),   # 600 of them: two waves
+])
+def test_more_heads_than_compute_units(heads, kv_heads, batch):
+    # with more heads than CUs the one-workgroup-per-head attention runs smaller workgroups so that
+    # several fit a CU; few tiles per wave and a ragged last tile
+    w = wl.WORKLOADS["llada8b_layer"].scaled(batch=batch, n_q_heads=heads, n_kv_heads=kv_heads, prompt=333, gen=64)
+    _run_block(w, n_steps=3)
+
+
 def test_fused_row_statistics_ignore_dominant_block_keys():
     # At the cache-update step the dense attention also supplies the scoring softmax's row statistics,
     # which run over the candidates only.  Here every query's own block key dominates its attention
