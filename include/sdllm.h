@@ -191,15 +191,6 @@ int32_t sdllm_dense_attn(const sdllm_shape_t* shape, const void* q_full, const i
                          const void* k_full, const void* v_full, void* out_full, const int64_t* out_full_stride,
                          void* stream);
 
-/*
- * Measurement aid for benchmarks (no counterpart in the paper): reads `bytes` bytes at `src` once
- * with the memory access pattern of the block-attention kernel (non-temporal 16-byte loads, one
- * 512-thread workgroup per contiguous chunk) and discards them.  Timing it gives the bandwidth the
- * memory system delivers for that pattern, the practical ceiling for sdllm_sparse_attn.  `src` must
- * be 16-byte aligned device memory; `sink` is 4 bytes of device memory (may be NULL).
- */
-int32_t sdllm_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream);
-
 #ifdef __cplusplus
 }
 #endif

@@ -4,6 +4,7 @@
 #include <math.h>
 
 #include "sdllm.h"
+#include "sdllm_bench.h"
 #include "sdllm_internal.h"
 
 using namespace sdllm;

@@ -5,6 +5,7 @@
 // 64, block lengths other than 32); it favours simplicity over speed.
 #include <type_traits>
 
+#include "attn_merge.h"
 #include "sdllm_internal.h"
 
 namespace sdllm {
@@ -73,7 +74,6 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const AttnParams p) {
 // partials mostly sit in L2 / MALL, so the merge is bound by how many loads are in flight).
 // block: kCombineThreads threads = kCombineThreads * 4 / d consecutive rows of the [B*Hq, nq] row list.
 constexpr int kCombineThreads = 256;
-typedef __attribute__((ext_vector_type(4))) float cf32x4;
 
 template <typename T>
 __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const AttnParams p, const int total_rows) {
@@ -91,53 +91,8 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const Att
   const int ml_ss = 2 * p.nq;
   const size_t po_ss = (size_t)p.nq * p.d;
 
-  // One sweep in batches of eight (then four) splits: all loads of a batch (max, sum, numerators) are
-  // requested before any is used, then folded into the running (max, sum, numerator) with the usual
-  // rescaling.  The partials were written a moment ago and sit in L2; what this kernel pays for is
-  // dependent round trips, and a separate pass for the overall max plus batches of four cost five
-  // or six of them (28 heads x 7 splits, 32k-prompt shape, partials written on other XCDs).
-  float m_tot = -INFINITY, l_tot = 0.f;
-  cf32x4 o = {0.f, 0.f, 0.f, 0.f};
-  auto fold = [&](auto batch, int s0) {
-    constexpr int NB = decltype(batch)::value;
-    float m_s[NB], l_s[NB];
-    cf32x4 o_s[NB];
-#pragma unroll
-    for (int u = 0; u < NB; ++u) {
-      const int s = min(s0 + u, p.n_split - 1);   // past the end (last batch only): re-read the last split, weight 0 below
-      m_s[u] = ml[s * ml_ss];
-      l_s[u] = ml[s * ml_ss + p.nq];
-      o_s[u] = *reinterpret_cast<const cf32x4*>(po + s * po_ss);
-    }
-    float m_new = m_tot;
-#pragma unroll
-    for (int u = 0; u < NB; ++u) m_new = fmaxf(m_new, m_s[u]);   // the re-read duplicates change nothing
-    if (m_new == -INFINITY) return;                              // nothing but empty splits so far
-    const float f_old = __builtin_amdgcn_exp2f(m_tot - m_new);  // 0 on the first batch
-    l_tot *= f_old;
-    o *= f_old;
-#pragma unroll
-    for (int u = 0; u < NB; ++u) {
-      const float f = (s0 + u < p.n_split && m_s[u] != -INFINITY) ? __builtin_amdgcn_exp2f(m_s[u] - m_new) : 0.f;
-      l_tot += f * l_s[u];
-      o += f * o_s[u];
-    }
-    m_tot = m_new;
-  };
-  int s0 = 0;
-  for (; s0 + 4 < p.n_split; s0 += 8) fold(std::integral_constant<int, 8>{}, s0);   // five or more left
-  if (s0 < p.n_split) fold(std::integral_constant<int, 4>{}, s0);
-  const float inv = 1.f / l_tot;
   T* out = (T*)p.out + b * p.o_sb + h * p.o_sh + row * p.o_sr + c4;
-  if constexpr (sizeof(T) == 2) {
-    typedef __attribute__((ext_vector_type(4))) __bf16 cbf16x4;
-    cbf16x4 v;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) v[r] = (__bf16)(o[r] * inv);
-    *reinterpret_cast<cbf16x4*>(out) = v;      // rows and row strides are 16-byte aligned, c4 a multiple of 4
-  } else {
-    *reinterpret_cast<cf32x4*>(out) = o * inv;
-  }
+  merge_row_piece<T>(ml, ml_ss, p.nq, po, po_ss, p.n_split, out);
 }
 
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, hipStream_t s) {

@@ -220,6 +220,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   float* pooled = p.pooled ? p.pooled + (size_t)row * p.n_cand + begin : nullptr;
   int32_t* out = idx_row + p.seg_out[seg];
   const int chunks = ITEMS > 0 ? ITEMS : (len + kSelThreads - 1) / kSelThreads;
+  if (len <= 0) return;   // an empty segment (no suffix after the last block, no prefix before the first): no load at all
 
   // 1. pooling
   const int half = p.pool_half;
@@ -396,6 +397,7 @@ __global__ __launch_bounds__(kSelThreads) void select_lds_kernel(const SelectPar
   float* pooled = p.pooled ? p.pooled + (size_t)row * p.n_cand + begin : nullptr;
   int32_t* out = idx_row + p.seg_out[seg];
   const int chunks = (len + kSelThreads - 1) / kSelThreads;   // <= kSelMaxItems (launcher)
+  if (len <= 0) return;   // an empty segment: no load at all
 
   // 1. pooling, kSelBatch chunks at a time
   const int half = p.pool_half;
@@ -527,6 +529,12 @@ static hipError_t launch_lds(const SelectParams& p, dim3 grid, int chunks, hipSt
 hipError_t launch_select(const SelectParams& p, hipStream_t s) {
   const int nx = p.n_seg + (p.tail_len > 0 ? 1 : 0);
   if (nx == 0 || p.rows == 0) return hipSuccess;
+  // every ranked segment and the unconditional tail lie inside a score row of n_cand candidates, so
+  // no workgroup reads past rows * n_cand floats of the score buffer
+  for (int i = 0; i < p.n_seg; ++i)
+    if (p.seg_begin[i] < 0 || p.seg_len[i] < 0 || p.seg_begin[i] + p.seg_len[i] > p.n_cand || p.seg_k[i] > p.seg_len[i])
+      return hipErrorInvalidValue;
+  if (p.tail_len > 0 && (p.tail_begin < 0 || p.tail_begin + p.tail_len > p.n_cand)) return hipErrorInvalidValue;
   int longest = 0;
   for (int i = 0; i < p.n_seg; ++i) longest = p.seg_len[i] > longest ? p.seg_len[i] : longest;
   const dim3 grid(nx, p.rows);

@@ -12,7 +12,7 @@ from oracle import sdllm_oracle as orc
 from paper_2508_02558_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "sdllm.h")
+INCLUDE = os.path.join(ROOT, "include")
 
 
 @pytest.fixture(scope="module")
@@ -24,9 +24,13 @@ def lib():
 
 
 def _declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sdllm_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(INCLUDE)):
+        if header.endswith(".h"):
+            text = open(os.path.join(INCLUDE, header)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names.update(re.findall(r"\b(sdllm_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):

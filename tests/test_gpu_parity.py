@@ -104,6 +104,37 @@ def test_llada_layer_last_block_has_no_suffix():
     _run_block(w, block_index=w.n_blocks - 1, n_steps=3)
 
 
+def test_last_block_with_exactly_sized_score_buffers():
+    # The last block of a generation has no suffix, so the suffix segment of every row is empty; the
+    # optional score / pooled outputs are exactly [B, Hkv, N] floats placed at the very end of a buffer
+    # whose following bytes hold NaN.  Nothing may be written behind them and the index set must not
+    # depend on where the score rows live.
+    _note("[case] last block, exactly sized score_out / pooled_out")
+    for pool_kernel, prompt in ((3, 1024), (5, 9000)):   # register-resident and LDS-resident select
+        w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=4, n_kv_heads=4, prompt=prompt, pool_kernel=pool_kernel)
+        bi = w.n_blocks - 1
+        inp = wl.make_block_inputs(w, 0, bi, 2, device=DEV)
+        shape = U.shape_for(w, bi)
+        gl = U.GpuLayer(shape, DEV)
+        assert shape.seq_len - shape.block_off - shape.block_len == 0
+        q = inp["q"][1].contiguous()
+        idx_ws, _, _ = gl.score_select(q, inp["k_full"], want_scores=False)
+        n = w.batch * w.n_kv_heads * gl.n_cand
+        guard = 64
+        buf_s = torch.full((n + guard,), float("nan"), device=DEV)
+        buf_p = torch.full((n + guard,), float("nan"), device=DEV)
+        gl.idx.fill_(-1)
+        B.sdllm_score_select(shape, q, inp["k_full"], gl.idx, buf_p[:n], buf_s[:n], gl.ws)
+        torch.cuda.synchronize()
+        assert (gl.idx[:, :, :gl.k_total].cpu().numpy() == idx_ws).all()
+        assert torch.isnan(buf_s[n:]).all() and torch.isnan(buf_p[n:]).all()
+        assert torch.isfinite(buf_s[:n]).all() and torch.isfinite(buf_p[:n]).all()
+        idx_orc, pooled_orc, _ = U.oracle_score_select(shape, q, inp["k_full"])
+        for g in range(w.n_kv_heads):
+            U.compare_index_rows(idx_ws[0, g], idx_orc[0, g], pooled_orc[0, g], w.seq_len, inp["block_off"], w.block,
+                                 U.ranked_segments(shape))
+
+
 def test_block_at_sequence_start_has_no_prefix():
     w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=4, n_kv_heads=4, prompt=0, gen=512)
     _run_block(w, block_index=0, n_steps=3)

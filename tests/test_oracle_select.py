@@ -20,11 +20,22 @@ def _ints(s):
 # ------------------------------------------------------------------ golden: hand-worked examples
 def test_hand_worked_8_token_examples(golden):
     rows = golden("select_8token.txt")
-    assert len(rows) == 5
+    assert len(rows) == 6
     for name, mode, s, r_or_k, layout, scores, pooled_exp, kept_exp in rows:
         scores, pooled_exp, kept_exp = _floats(scores), _floats(pooled_exp), _ints(kept_exp)
         s = int(s)
-        if layout.startswith("seg:"):
+        if mode == orc.PREFIX_ONLY:
+            # Alg. 4 through the oracle's only entry that implements it.  One head, head_dim 1, both block
+            # queries equal to 1 and scale 1: in "logit_mean" mode the score of a key IS its value, so the
+            # hand-worked scores go in as keys (the block's own two keys are arbitrary).
+            o, b, L = (int(kv.split("=")[1]) for kv in layout.split(","))
+            keys = np.concatenate([scores[:o], [7.0, -3.0], scores[o:]])
+            idx, pooled, score = orc.score_select(np.ones((1, b, 1)), keys.reshape(1, L, 1), o, b, float(r_or_k), s,
+                                                  orc.LOGIT_MEAN, scale=1.0, evict_scope=orc.PREFIX_ONLY)
+            np.testing.assert_allclose(score[0], scores[:o], rtol=0, atol=1e-15, err_msg=name)
+            np.testing.assert_allclose(pooled[0], pooled_exp, rtol=0, atol=1e-15, err_msg=name)
+            assert idx[0].tolist() == kept_exp, name
+        elif layout.startswith("seg:"):
             pooled = orc.pool_1d(scores, s)
             np.testing.assert_allclose(pooled, pooled_exp, rtol=0, atol=0, err_msg=name)
             kept = orc.top_k_lowest_position(pooled, int(r_or_k))
@@ -178,7 +189,8 @@ def test_candidate_positions():
 
 def test_prefix_only_eviction_keeps_the_whole_suffix():
     """Alg. 4: the prefix is ranked exactly as a sequence that ends with the block would be, and every
-    suffix position is appended."""
+    suffix position is appended.  (The hand-worked row `alg4_prefix_only` of the golden file pins the
+    same branch without going through the oracle's own bidirectional path.)"""
     rng = np.random.default_rng(21)
     hq, hkv, b, d, L, o = 4, 2, 4, 8, 30, 12
     q = rng.standard_normal((hq, b, d)); k = rng.standard_normal((hkv, L, d))
