@@ -36,6 +36,7 @@ extern "C" {
 #define SDLLM_ERR_UNSUPPORTED (-2) /* a legal request this build has no kernel for */
 #define SDLLM_ERR_WORKSPACE (-3)   /* workspace pointer null or smaller than sdllm_workspace_bytes() */
 #define SDLLM_ERR_HIP (-4)         /* a HIP launch reported an error */
+#define SDLLM_ERR_STATIC_LIMIT (-5) /* sdllm_sparse_attn_noalloc: the request needs more than SDLLM_STATIC_SCRATCH_BYTES */
 
 /* element types of Q/K/V/O (accumulation is always fp32) */
 #define SDLLM_BF16 0
@@ -161,6 +162,22 @@ int32_t sdllm_compact_kv(const sdllm_shape_t* shape, const void* k_full, const v
 int32_t sdllm_sparse_attn(const sdllm_shape_t* shape, const void* q_blk, const void* k_cache, const void* v_cache,
                           int32_t n_cached, const void* k_blk, const void* v_blk, void* out, void* ws,
                           size_t ws_bytes, void* stream);
+
+/*
+ * sdllm_sparse_attn for callers that cannot allocate or size a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results, but the split-KV partials live in an array of SDLLM_STATIC_SCRATCH_BYTES
+ * that is part of the library's device image (every GPU the library runs on holds one copy until the
+ * process ends).  The call allocates nothing and frees nothing.  A shape whose launch plan needs
+ * more scratch than that returns SDLLM_ERR_STATIC_LIMIT and enqueues nothing (use sdllm_sparse_attn
+ * with a workspace then).  All calls on one GPU share that GPU's array: calls that overlap in time
+ * on one GPU (different streams, or concurrently replayed graphs) race and are not allowed.  The
+ * first call on each device resolves the array's address and must not be made under stream capture.
+ */
+#define SDLLM_STATIC_SCRATCH_BYTES (8u << 20)
+int32_t sdllm_sparse_attn_noalloc(const sdllm_shape_t* shape, const void* q_blk, const void* k_cache,
+                                  const void* v_cache, int32_t n_cached, const void* k_blk, const void* v_blk,
+                                  void* out, void* stream);
 
 /*
  * One denoising step of one layer (Alg. 2/5 -> Alg. 3 -> Alg. 1).  state = cache_state(step, delay).

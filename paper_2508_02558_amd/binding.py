@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(HERE, "libsdllm.so")
 
 # constants of include/sdllm.h
 SDLLM_OK = 0
-SDLLM_ERR_INVALID_ARG, SDLLM_ERR_UNSUPPORTED, SDLLM_ERR_WORKSPACE, SDLLM_ERR_HIP = -1, -2, -3, -4
+SDLLM_ERR_INVALID_ARG, SDLLM_ERR_UNSUPPORTED, SDLLM_ERR_WORKSPACE, SDLLM_ERR_HIP, SDLLM_ERR_STATIC_LIMIT = -1, -2, -3, -4, -5
+SDLLM_STATIC_SCRATCH_BYTES = 8 << 20
 SDLLM_BF16, SDLLM_F32 = 0, 1
 SDLLM_SOFTMAX_MEAN, SDLLM_LOGIT_MEAN = 0, 1
 SDLLM_PER_SEGMENT, SDLLM_JOINT = 0, 1
@@ -28,7 +29,7 @@ SDLLM_OP_SCORE_SELECT, SDLLM_OP_COMPACT_KV, SDLLM_OP_SPARSE_ATTN, SDLLM_OP_BLOCK
 
 EXPORTED = ("sdllm_error_string", "sdllm_version", "sdllm_retained_count", "sdllm_workspace_bytes",
             "sdllm_cache_state", "sdllm_score_select", "sdllm_compact_kv", "sdllm_sparse_attn",
-            "sdllm_block_step", "sdllm_dense_attn", "sdllm_stream_read_probe")
+            "sdllm_sparse_attn_noalloc", "sdllm_block_step", "sdllm_dense_attn", "sdllm_stream_read_probe")
 
 
 class sdllm_shape_t(ctypes.Structure):
@@ -81,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.sdllm_compact_kv.argtypes = [shp, vp, vp, vp, vp, vp, vp]
     lib.sdllm_sparse_attn.restype = i32
     lib.sdllm_sparse_attn.argtypes = [shp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.sdllm_sparse_attn_noalloc.restype = i32
+    lib.sdllm_sparse_attn_noalloc.argtypes = [shp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.sdllm_block_step.restype = i32
     lib.sdllm_block_step.argtypes = [shp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, i32p]
     lib.sdllm_dense_attn.restype = i32
@@ -190,6 +193,12 @@ def sdllm_sparse_attn(shape, q_blk, k_cache, v_cache, n_cached, k_blk, v_blk, ou
                                     _ptr(k_blk), _ptr(v_blk), _ptr(out), _ptr(ws),
                                     ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "sdllm_sparse_attn")
+
+
+def sdllm_sparse_attn_noalloc(shape, q_blk, k_cache, v_cache, n_cached, k_blk, v_blk, out, stream=None) -> None:
+    _check(load().sdllm_sparse_attn_noalloc(ctypes.byref(shape), _ptr(q_blk), _ptr(k_cache), _ptr(v_cache), n_cached,
+                                            _ptr(k_blk), _ptr(v_blk), _ptr(out), _stream(stream)),
+           "sdllm_sparse_attn_noalloc")
 
 
 def sdllm_block_step(shape, step_in_block, delay, q_blk, k_in, v_in, idx, k_cache, v_cache, out, ws,

@@ -352,6 +352,39 @@ BlockStepWs plan_block_step(const sdllm_shape_t& s) {
 
 }  // namespace
 
+// ---------------------------------------------------------------- static scratch (sdllm_sparse_attn_noalloc)
+// The array is part of the device image: one copy per GPU, at its own address, alive until the
+// process ends.  In host code the name `scratch` is only a handle for hipGetSymbolAddress; kernels
+// and launch parameters get the per-device address resolved here.  The declaration carries no `used`
+// attribute on purpose: the compiler gives a static device variable that host code refers to external
+// linkage in the device image, which is how the runtime finds it, and leaves a `used` one local (the
+// runtime then aborts in hipGetSymbolAddress).
+static __device__ __align__(256) unsigned char scratch[SDLLM_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Address of the current device's copy of `scratch` (resolved once per device, with that device current).
+hipError_t static_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // concurrent first calls resolve the same address
+  }
+  *out = ptr;
+  return hipSuccess;
+}
+
+}  // namespace
+
 // ================================================================ exported functions
 extern "C" {
 
@@ -362,6 +395,7 @@ const char* sdllm_error_string(int32_t status) {
     case SDLLM_ERR_UNSUPPORTED: return "unsupported shape or type";
     case SDLLM_ERR_WORKSPACE: return "workspace missing or too small";
     case SDLLM_ERR_HIP: return "HIP launch failed";
+    case SDLLM_ERR_STATIC_LIMIT: return "request exceeds the static scratch of sdllm_sparse_attn_noalloc";
     default: return "unknown status";
   }
 }
@@ -458,6 +492,20 @@ int32_t sdllm_sparse_attn(const sdllm_shape_t* shape, const void* q_blk, const v
   KvSegment a{k_cache, v_cache, s.cache_stride[0], s.cache_stride[1], s.cache_stride[2], n_cached};
   KvSegment b{k_blk, v_blk, s.blk_stride[0], s.blk_stride[1], s.blk_stride[2], s.block_len};
   return run_attn(s, q_blk, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int32_t sdllm_sparse_attn_noalloc(const sdllm_shape_t* shape, const void* q_blk, const void* k_cache,
+                                  const void* v_cache, int32_t n_cached, const void* k_blk, const void* v_blk,
+                                  void* out, void* stream) {
+  const int32_t st = check_shape(shape);
+  if (st != SDLLM_OK) return st;
+  if (n_cached < 0) return SDLLM_ERR_INVALID_ARG;
+  const sdllm_shape_t& s = *shape;
+  const size_t need = plan_attn(s, n_cached, s.cache_stride[2], s.block_len, s.blk_stride[2]).ws_bytes();
+  if (need > SDLLM_STATIC_SCRATCH_BYTES) return SDLLM_ERR_STATIC_LIMIT;
+  void* ptr = nullptr;
+  if (static_scratch(&ptr) != hipSuccess) return SDLLM_ERR_HIP;
+  return sdllm_sparse_attn(shape, q_blk, k_cache, v_cache, n_cached, k_blk, v_blk, out, ptr, SDLLM_STATIC_SCRATCH_BYTES, stream);
 }
 
 int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int32_t delay, const void* q_blk,

@@ -122,6 +122,36 @@ def test_null_pointers_and_small_workspace_are_rejected_before_any_launch(lib):
     assert lib.sdllm_sparse_attn(sp, fake, z, z, -1, fake, fake, fake, z, 0, z) == B.SDLLM_ERR_INVALID_ARG
 
 
+def test_noalloc_entry_rejects_requests_beyond_its_static_scratch(lib):
+    # batch 8 of a 28/4-head shape with 8000 cached keys runs the shared-tile kernel with 8 key splits:
+    # 1792 partial slots of 16.25 KB, far beyond the 8 MiB array.  Rejected on the host, nothing enqueued.
+    s = B.make_shape(batch=8, n_q_heads=28, n_kv_heads=4, head_dim=128, seq_len=20000, block_off=12000, block_len=32,
+                     dtype=B.SDLLM_BF16, cache_rows=8000)
+    assert B.sdllm_workspace_bytes(s, B.SDLLM_OP_SPARSE_ATTN, 8000) > B.SDLLM_STATIC_SCRATCH_BYTES
+    fake = ctypes.c_void_p(0x1000)
+    z = ctypes.c_void_p(None)
+    assert lib.sdllm_sparse_attn_noalloc(ctypes.byref(s), fake, fake, fake, 8000, fake, fake, fake, z) == B.SDLLM_ERR_STATIC_LIMIT
+    assert "static scratch" in B.error_string(B.SDLLM_ERR_STATIC_LIMIT)
+    assert lib.sdllm_sparse_attn_noalloc(ctypes.byref(s), fake, fake, fake, -1, fake, fake, fake, z) == B.SDLLM_ERR_INVALID_ARG
+
+
+def test_static_scratch_is_visible_in_the_device_image(lib, tmp_path):
+    # hipGetSymbolAddress looks the array up by name in the gfx950 code object: it has to be a GLOBAL
+    # symbol there (a LOCAL one makes the runtime abort on the first sdllm_sparse_attn_noalloc call)
+    obj = os.path.join(ROOT, "paper_2508_02558_amd", "_build", "api.o")
+    objdump, readelf = "/opt/rocm/llvm/bin/llvm-objdump", "/opt/rocm/llvm/bin/llvm-readelf"
+    if not (os.path.exists(obj) and os.path.exists(objdump) and os.path.exists(readelf)):
+        pytest.skip("needs the build directory and the LLVM binutils")
+    local = tmp_path / "api.o"
+    local.write_bytes(open(obj, "rb").read())
+    subprocess.check_call([objdump, "--offloading", str(local)], cwd=tmp_path, stdout=subprocess.DEVNULL)
+    images = [f for f in os.listdir(tmp_path) if "gfx950" in f]
+    assert images, os.listdir(tmp_path)
+    syms = subprocess.check_output([readelf, "--dyn-syms", str(tmp_path / images[0])], text=True)
+    rows = [ln.split() for ln in syms.splitlines() if ln.strip().endswith("scratch")]
+    assert rows and all(r[4] == "GLOBAL" and int(r[2]) == B.SDLLM_STATIC_SCRATCH_BYTES for r in rows), syms
+
+
 def test_workspace_sizes(lib):
     s = _shape()
     for op in (B.SDLLM_OP_SCORE_SELECT, B.SDLLM_OP_COMPACT_KV, B.SDLLM_OP_SPARSE_ATTN, B.SDLLM_OP_BLOCK_STEP):
