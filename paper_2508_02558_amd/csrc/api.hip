@@ -2,6 +2,7 @@
 // method lives here except the retained-count rule and the cache-state schedule, which are host
 // logic by nature (Alg. 1 step 9; Alg. 2 / Alg. 5).
 #include <math.h>
+#include <stdlib.h>
 
 #include "sdllm.h"
 #include "sdllm_bench.h"
@@ -155,19 +156,30 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
     // the grid within one workgroup per CU (an eight-wave workgroup fills a CU's LDS, so workgroup
     // number 257 waits for a whole round: 56 heads x 4 splits 15.1 us, x 5 splits 22.3 us), at most 6
     // (8 from 256 tiles per head on: 28 heads x 261 tiles, 20.4 us with 6 splits, 19.0 us with 8),
-    // and at least eleven tiles per workgroup.  A split costs fp32 partials and a second launch of
-    // about 4 us, which 21 tiles (672 keys) do not repay; beyond that batch-1 shapes are pure
-    // latency and a wave with one or two tiles beats a longer chain (1280 keys x 32 heads, dense
-    // step: 16.2 -> 14.8 us with 3 splits instead of 2; 28/4 heads x 4352 keys: 17.2 -> 15.0 us with
-    // 6 or 7 instead of 4).  From 129 heads on there is one workgroup per head.
+    // and a minimum of tiles per workgroup (below).  Batch-1 shapes are pure latency and a wave with
+    // one or two tiles beats a longer chain (28/4 heads x 4352 keys: 17.2 -> 15.0 us with 6 or 7 splits
+    // instead of 4).  From 129 heads on there is one workgroup per head.
     int n_split = kNumCUs / heads;
     const int most = tiles >= 256 ? 8 : 6;
     if (n_split > most) n_split = most;
-    const int max_split = tiles / 11;
+    // A split costs fp32 partials and a second launch of about 4 us: with up to 32 heads (where three or
+    // more splits fit) seven tiles per workgroup repay it, one tile per wave or two (32 heads x 21 tiles,
+    // sparse step 12.1 -> 11.6 us, dense step over 41 tiles 14.0 -> 12.9 us with 3 splits); from 64 heads
+    // on it takes eleven (128 heads x 21 tiles: 14.5 us unsplit, 15.9 us with 2 splits).
+    const int max_split = tiles / (heads <= 32 ? 7 : 11);
     if (n_split > max_split) n_split = max_split;
     if (n_split < 1) n_split = 1;
+#ifdef SDLLM_TUNING   // development builds only: launch-plan overrides from the environment
+    if (const char* e = getenv("SDLLM_T_NSPLIT")) { n_split = atoi(e); if (n_split > tiles) n_split = tiles; if (n_split < 1) n_split = 1; }
+#endif
     pl.tiles_per_split = (tiles + n_split - 1) / n_split;
     pl.waves = pl.tiles_per_split < kMaxWavesPerWg ? pl.tiles_per_split : kMaxWavesPerWg;
+    // split workgroups: two tiles per wave when there are fewer than sixteen (28 heads x 69 tiles in 6
+    // splits: 12.6 -> 12.35 us with six waves instead of eight; the in-workgroup merge is smaller)
+    if (n_split > 1) { const int w2 = (pl.tiles_per_split + 1) / 2; pl.waves = w2 < kMaxWavesPerWg ? w2 : kMaxWavesPerWg; }
+#ifdef SDLLM_TUNING
+    if (const char* e = getenv("SDLLM_T_WAVES")) { pl.waves = atoi(e); if (pl.waves > pl.tiles_per_split) pl.waves = pl.tiles_per_split; }
+#endif
     // One workgroup per head: fewer, longer-running waves measured faster than eight (smaller merge at
     // the end, 40-48 KB instead of 64 KB of loads in flight per CU).  With more heads than CUs four
     // waves let two workgroups share a CU, so one streams while the other merges and writes, and no
