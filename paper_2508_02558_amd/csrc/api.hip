@@ -241,9 +241,34 @@ struct ScorePlan {
   bool mfma;
   int n_scored;       // candidates that get a score
   int n_part, tiles_per_part, waves;
-  size_t score_bytes, pooled_bytes, ml_bytes;
-  size_t ws_bytes() const { return score_bytes + pooled_bytes + ml_bytes; }
+  // workspace: scores, the pooled scores' integer keys, softmax row statistics, the thresholds of the
+  // selection and (segments too long for one workgroup) its bin lists
+  size_t score_bytes, keys_bytes, ml_bytes, thr_bytes, bins_bytes;
+  size_t ws_bytes() const { return score_bytes + keys_bytes + ml_bytes + thr_bytes + bins_bytes; }
 };
+
+// The ranked segments and the unconditional tail of the selection for this shape (Alg. 1 steps 8-10;
+// Alg. 4 keeps the suffix whole).
+void fill_segments(const sdllm_shape_t& s, const Counts& c, SelectParams& q) {
+  q.rows = s.batch * s.n_kv_heads;
+  q.n_cand = c.n_cand;
+  q.k_total = c.k_total;
+  q.pool_half = (s.pool_kernel - 1) / 2;
+  q.avg_pool = s.pool_mode == SDLLM_AVG_POOL;
+  q.block_off = s.block_off; q.block_len = s.block_len;
+  if (s.evict_scope == SDLLM_EVICT_PREFIX_ONLY) {
+    q.n_seg = 1;
+    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
+    q.tail_begin = c.n_pre; q.tail_len = c.n_suf; q.tail_out = c.k_pre;
+  } else if (s.select_mode == SDLLM_PER_SEGMENT) {
+    q.n_seg = 2;
+    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
+    q.seg_begin[1] = c.n_pre; q.seg_len[1] = c.n_suf; q.seg_k[1] = c.k_suf; q.seg_out[1] = c.k_pre;
+  } else {
+    q.n_seg = 1;
+    q.seg_begin[0] = 0; q.seg_len[0] = c.n_cand; q.seg_k[0] = c.k_total; q.seg_out[0] = 0;
+  }
+}
 
 ScorePlan plan_score(const sdllm_shape_t& s) {
   const Counts c = counts_of(s);
@@ -251,7 +276,13 @@ ScorePlan plan_score(const sdllm_shape_t& s) {
   pl.n_scored = s.evict_scope == SDLLM_EVICT_PREFIX_ONLY ? c.n_pre : c.n_cand;
   const size_t rows = (size_t)s.batch * s.n_kv_heads;
   pl.score_bytes = align_up(rows * c.n_cand * sizeof(float));
-  pl.pooled_bytes = pl.score_bytes;
+  pl.keys_bytes = pl.score_bytes;
+  pl.thr_bytes = align_up(rows * 4 * sizeof(uint32_t));
+  {
+    SelectParams q{};
+    fill_segments(s, c, q);
+    pl.bins_bytes = align_up(select_bins_words(q) * sizeof(uint32_t));
+  }
   pl.mfma = s.dtype == SDLLM_BF16 && s.head_dim == 128 && s.block_len == 32 &&
             score_mfma_supports_group(s.n_q_heads / s.n_kv_heads) && seg_fits_u32(s.kv_stride[2], s.seq_len, 2);
   pl.n_part = 1;
@@ -282,19 +313,29 @@ int32_t check_q(const sdllm_shape_t& s, const void* q) {
   return SDLLM_OK;
 }
 
-// Alg. 1 steps 2-10.  ext_ml != null: the softmax row statistics over the candidates were already
-// produced (ext_parts partials per row) and only the column reduction and the selection run.
+// Alg. 1 steps 2-10 and, when `gather` is given, steps 12-14 fused into the selection's last stage.
+// ext_ml != null: the softmax row statistics over the candidates were already produced (ext_parts
+// partials per row) and only the column reduction and the selection run.
+struct GatherArgs { const void* k; const void* v; void* kc; void* vc; };
+
 int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void* k_full, int32_t* idx_out,
                           float* pooled_out, float* score_out, void* ws, size_t ws_bytes, hipStream_t hs,
-                          float* ext_ml, int ext_parts) {
+                          float* ext_ml, int ext_parts, const GatherArgs* gather) {
   const Counts c = counts_of(s);
   const ScorePlan pl = plan_score(s);
   if (!ws || ws_bytes < pl.ws_bytes() || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return SDLLM_ERR_WORKSPACE;
   if (c.n_cand == 0) return SDLLM_OK;
 
-  float* score = score_out ? score_out : (float*)ws;
-  float* pooled = pooled_out ? pooled_out : (float*)((char*)ws + pl.score_bytes);
-  float* ml = (float*)((char*)ws + pl.score_bytes + pl.pooled_bytes);
+  char* at = (char*)ws;
+  float* score = score_out ? score_out : (float*)at;
+  at += pl.score_bytes;
+  uint32_t* keys = (uint32_t*)at;
+  at += pl.keys_bytes;
+  float* ml = (float*)at;
+  at += pl.ml_bytes;
+  uint32_t* thr = (uint32_t*)at;
+  at += pl.thr_bytes;
+  uint32_t* bins = pl.bins_bytes ? (uint32_t*)at : nullptr;
 
   ScoreParams sp{};
   sp.q = q_blk; sp.k = k_full;
@@ -317,26 +358,16 @@ int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void*
   if (e != hipSuccess) return SDLLM_ERR_HIP;
 
   SelectParams q{};
-  q.score = score; q.pooled = pooled; q.idx = idx_out;
-  q.rows = s.batch * s.n_kv_heads;
-  q.n_cand = c.n_cand;
-  q.k_total = c.k_total;
-  q.pool_half = (s.pool_kernel - 1) / 2;
-  q.avg_pool = s.pool_mode == SDLLM_AVG_POOL;
-  q.block_off = s.block_off; q.block_len = s.block_len;
-  if (s.evict_scope == SDLLM_EVICT_PREFIX_ONLY) {
-    q.n_seg = 1;
-    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
-    q.tail_begin = c.n_pre; q.tail_len = c.n_suf; q.tail_out = c.k_pre;
-  } else if (s.select_mode == SDLLM_PER_SEGMENT) {
-    q.n_seg = 2;
-    q.seg_begin[0] = 0; q.seg_len[0] = c.n_pre; q.seg_k[0] = c.k_pre; q.seg_out[0] = 0;
-    q.seg_begin[1] = c.n_pre; q.seg_len[1] = c.n_suf; q.seg_k[1] = c.k_suf; q.seg_out[1] = c.k_pre;
-  } else {
-    q.n_seg = 1;
-    q.seg_begin[0] = 0; q.seg_len[0] = c.n_cand; q.seg_k[0] = c.k_total; q.seg_out[0] = 0;
+  fill_segments(s, c, q);
+  q.score = score; q.pooled = pooled_out; q.keys = keys; q.thr = thr; q.bins = bins; q.idx = idx_out;
+  if (gather) {
+    const int es = elem_size(s.dtype);
+    q.k = gather->k; q.v = gather->v; q.kc = gather->kc; q.vc = gather->vc;
+    q.s_sb = s.kv_stride[0] * es; q.s_sh = s.kv_stride[1] * es; q.s_sr = s.kv_stride[2] * es;
+    q.c_sb = s.cache_stride[0] * es; q.c_sh = s.cache_stride[1] * es; q.c_sr = s.cache_stride[2] * es;
+    q.hkv = s.n_kv_heads;
+    q.row_bytes = s.head_dim * es;
   }
-  if (!pooled_out && !select_needs_pooled_buffer(q)) q.pooled = nullptr;   // the pooled row then lives in registers only
   e = launch_select(q, hs);
   return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
 }
@@ -462,7 +493,7 @@ int32_t sdllm_score_select(const sdllm_shape_t* shape, const void* q_blk, const 
   if ((st = check_q(s, q_blk)) != SDLLM_OK) return st;
   if (!k_full || !aligned16(k_full) || !row_stride_ok(s.kv_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
   if (counts_of(s).k_total > 0 && !idx_out) return SDLLM_ERR_INVALID_ARG;
-  return score_select_impl(s, q_blk, k_full, idx_out, pooled_out, score_out, ws, ws_bytes, (hipStream_t)stream, nullptr, 0);
+  return score_select_impl(s, q_blk, k_full, idx_out, pooled_out, score_out, ws, ws_bytes, (hipStream_t)stream, nullptr, 0, nullptr);
 }
 
 int32_t sdllm_compact_kv(const sdllm_shape_t* shape, const void* k_full, const void* v_full, const int32_t* idx,
@@ -556,10 +587,12 @@ int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int3
   }
   if (st != SDLLM_OK || state == SDLLM_STATE_FULL) return st;
   if (!row_stride_ok(s.q_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
-  st = score_select_impl(s, q_blk, k_in, idx, nullptr, nullptr, ws, w.base, (hipStream_t)stream,
-                         w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts);
-  if (st != SDLLM_OK) return st;
-  return sdllm_compact_kv(shape, k_in, v_in, idx, k_cache, v_cache, stream);
+  // the selection's last stage writes the index set and gathers the retained K/V rows into the cache
+  if (c.k_total > 0 && (!aligned16(k_cache) || !aligned16(v_cache) || !row_stride_ok(s.cache_stride, s.head_dim)))
+    return SDLLM_ERR_INVALID_ARG;
+  const GatherArgs gather{k_in, v_in, k_cache, v_cache};
+  return score_select_impl(s, q_blk, k_in, idx, nullptr, nullptr, ws, w.base, (hipStream_t)stream,
+                           w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts, c.k_total > 0 ? &gather : nullptr);
 }
 
 int32_t sdllm_dense_attn(const sdllm_shape_t* shape, const void* q_full, const int64_t* q_full_stride,

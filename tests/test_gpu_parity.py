@@ -264,6 +264,47 @@ def test_select_long_segments(prompt, gen, block_index, modes):
         assert (gl.idx[:, :, :gl.k_total].cpu().numpy() == idx_gpu).all()
 
 
+@pytest.mark.parametrize("prompt,modes", [
+    (3000, {}),                                                                   # one workgroup per segment
+    (20000, {}),                                                                  # pooling spread over 10 workgroups
+    (20000, dict(select_mode=B.SDLLM_JOINT, k_rounding=B.SDLLM_FLOOR)),           # one joint segment across the seam
+    (70000, dict(evict_scope=B.SDLLM_EVICT_PREFIX_ONLY)),                         # 35 pooling workgroups, suffix kept whole
+])
+def test_exact_ties_across_workgroup_boundaries(prompt, modes):
+    # Keys that take only five distinct values, in runs of 37 positions: every score is one of five
+    # levels, each level holds a fifth of the candidates, and the k-th value falls inside a level whose
+    # members are spread over the whole segment.  The retained members of that level must be exactly
+    # its lowest positions, which the emission can only get right if its counts of equal entries are
+    # exact across every pooling-workgroup (2048) and emission-workgroup (1024) boundary.  Identical keys
+    # give bit-identical scores on both sides, so the index sets are compared entry by entry.
+    _note(f"[case] exact ties prompt={prompt} modes={modes}")
+    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=2, n_kv_heads=2, prompt=prompt, gen=96, retention=0.3)
+    inp = wl.make_block_inputs(w, 0, 1, 2, device=DEV)
+    shape = U.shape_for(w, 1, **modes)
+    gl = U.GpuLayer(shape, DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(prompt)
+    levels = torch.randn(w.batch, w.n_kv_heads, 5, w.head_dim, device=DEV, generator=g).bfloat16()
+    which = (torch.arange(w.seq_len, device=DEV) // 37) % 5
+    k_full = levels[:, :, which]
+    q = inp["q"][1].contiguous()
+    idx_gpu, pooled, _ = gl.score_select(q, k_full)
+    idx_orc, pooled_orc, _ = U.oracle_score_select(shape, q, k_full)
+    for begin, length, k in U.ranked_segments(shape):
+        if k >= 0:
+            assert np.unique(pooled_orc[:, :, begin:begin + length]).size <= 5 * w.n_kv_heads
+            assert torch.unique(pooled[:, :, begin:begin + length]).numel() <= 5 * w.n_kv_heads
+    assert idx_gpu.shape == idx_orc.shape
+    assert (idx_gpu == idx_orc).all(), f"{int((idx_gpu != idx_orc).sum())} entries differ"
+    # all-zero queries: one level for everybody, the threshold bin holds the whole segment
+    idx0, _, _ = gl.score_select(torch.zeros_like(q), k_full)
+    want = []
+    for begin, length, k in U.ranked_segments(shape):
+        cand = orc.candidate_positions(w.seq_len, inp["block_off"], w.block)[begin:begin + length]
+        want.append(cand if k < 0 else cand[:k])
+    assert (idx0 == np.concatenate(want)[None, None]).all()
+
+
 def test_scores_match_oracle_values():
     _note("[case] score / pooled values")
     # every group size has its own instantiation of the two scoring passes (the stand-alone entry
