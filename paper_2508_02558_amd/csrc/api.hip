@@ -241,10 +241,10 @@ struct ScorePlan {
   bool mfma;
   int n_scored;       // candidates that get a score
   int n_part, tiles_per_part, waves;
-  // workspace: scores, the pooled scores' integer keys, softmax row statistics, the thresholds of the
-  // selection and (segments too long for one workgroup) its bin lists
-  size_t score_bytes, keys_bytes, ml_bytes, thr_bytes, bins_bytes;
-  size_t ws_bytes() const { return score_bytes + keys_bytes + ml_bytes + thr_bytes + bins_bytes; }
+  // workspace: scores, softmax row statistics and, for segments too long for one workgroup, the selection's
+  // key buffer, thresholds, bin lists and chunk offsets
+  size_t score_bytes, ml_bytes, keys_bytes, thr_bytes, bins_bytes, offs_bytes;
+  size_t ws_bytes() const { return score_bytes + ml_bytes + keys_bytes + thr_bytes + bins_bytes + offs_bytes; }
 };
 
 // The ranked segments and the unconditional tail of the selection for this shape (Alg. 1 steps 8-10;
@@ -276,12 +276,14 @@ ScorePlan plan_score(const sdllm_shape_t& s) {
   pl.n_scored = s.evict_scope == SDLLM_EVICT_PREFIX_ONLY ? c.n_pre : c.n_cand;
   const size_t rows = (size_t)s.batch * s.n_kv_heads;
   pl.score_bytes = align_up(rows * c.n_cand * sizeof(float));
-  pl.keys_bytes = pl.score_bytes;
-  pl.thr_bytes = align_up(rows * 4 * sizeof(uint32_t));
   {
     SelectParams q{};
     fill_segments(s, c, q);
-    pl.bins_bytes = align_up(select_bins_words(q) * sizeof(uint32_t));
+    const SelectWorkspace sw = select_workspace(q);
+    pl.keys_bytes = align_up(sw.keys * sizeof(uint32_t));
+    pl.thr_bytes = align_up(sw.thr * sizeof(uint32_t));
+    pl.bins_bytes = align_up(sw.bins * sizeof(uint32_t));
+    pl.offs_bytes = align_up(sw.offs * sizeof(uint32_t));
   }
   pl.mfma = s.dtype == SDLLM_BF16 && s.head_dim == 128 && s.block_len == 32 &&
             score_mfma_supports_group(s.n_q_heads / s.n_kv_heads) && seg_fits_u32(s.kv_stride[2], s.seq_len, 2);
@@ -313,14 +315,11 @@ int32_t check_q(const sdllm_shape_t& s, const void* q) {
   return SDLLM_OK;
 }
 
-// Alg. 1 steps 2-10 and, when `gather` is given, steps 12-14 fused into the selection's last stage.
-// ext_ml != null: the softmax row statistics over the candidates were already produced (ext_parts
-// partials per row) and only the column reduction and the selection run.
-struct GatherArgs { const void* k; const void* v; void* kc; void* vc; };
-
+// Alg. 1 steps 2-10.  ext_ml != null: the softmax row statistics over the candidates were already
+// produced (ext_parts partials per row) and only the column reduction and the selection run.
 int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void* k_full, int32_t* idx_out,
                           float* pooled_out, float* score_out, void* ws, size_t ws_bytes, hipStream_t hs,
-                          float* ext_ml, int ext_parts, const GatherArgs* gather) {
+                          float* ext_ml, int ext_parts) {
   const Counts c = counts_of(s);
   const ScorePlan pl = plan_score(s);
   if (!ws || ws_bytes < pl.ws_bytes() || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return SDLLM_ERR_WORKSPACE;
@@ -329,13 +328,15 @@ int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void*
   char* at = (char*)ws;
   float* score = score_out ? score_out : (float*)at;
   at += pl.score_bytes;
-  uint32_t* keys = (uint32_t*)at;
-  at += pl.keys_bytes;
   float* ml = (float*)at;
   at += pl.ml_bytes;
-  uint32_t* thr = (uint32_t*)at;
+  uint32_t* keys = pl.keys_bytes ? (uint32_t*)at : nullptr;
+  at += pl.keys_bytes;
+  uint32_t* thr = pl.thr_bytes ? (uint32_t*)at : nullptr;
   at += pl.thr_bytes;
   uint32_t* bins = pl.bins_bytes ? (uint32_t*)at : nullptr;
+  at += pl.bins_bytes;
+  uint32_t* offs = pl.offs_bytes ? (uint32_t*)at : nullptr;
 
   ScoreParams sp{};
   sp.q = q_blk; sp.k = k_full;
@@ -359,15 +360,8 @@ int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void*
 
   SelectParams q{};
   fill_segments(s, c, q);
-  q.score = score; q.pooled = pooled_out; q.keys = keys; q.thr = thr; q.bins = bins; q.idx = idx_out;
-  if (gather) {
-    const int es = elem_size(s.dtype);
-    q.k = gather->k; q.v = gather->v; q.kc = gather->kc; q.vc = gather->vc;
-    q.s_sb = s.kv_stride[0] * es; q.s_sh = s.kv_stride[1] * es; q.s_sr = s.kv_stride[2] * es;
-    q.c_sb = s.cache_stride[0] * es; q.c_sh = s.cache_stride[1] * es; q.c_sr = s.cache_stride[2] * es;
-    q.hkv = s.n_kv_heads;
-    q.row_bytes = s.head_dim * es;
-  }
+  q.score = score; q.pooled = pooled_out; q.idx = idx_out;
+  q.keys = keys; q.thr = thr; q.bins = bins; q.offs = offs;
   e = launch_select(q, hs);
   return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
 }
@@ -493,7 +487,7 @@ int32_t sdllm_score_select(const sdllm_shape_t* shape, const void* q_blk, const 
   if ((st = check_q(s, q_blk)) != SDLLM_OK) return st;
   if (!k_full || !aligned16(k_full) || !row_stride_ok(s.kv_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
   if (counts_of(s).k_total > 0 && !idx_out) return SDLLM_ERR_INVALID_ARG;
-  return score_select_impl(s, q_blk, k_full, idx_out, pooled_out, score_out, ws, ws_bytes, (hipStream_t)stream, nullptr, 0, nullptr);
+  return score_select_impl(s, q_blk, k_full, idx_out, pooled_out, score_out, ws, ws_bytes, (hipStream_t)stream, nullptr, 0);
 }
 
 int32_t sdllm_compact_kv(const sdllm_shape_t* shape, const void* k_full, const void* v_full, const int32_t* idx,
@@ -587,12 +581,10 @@ int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int3
   }
   if (st != SDLLM_OK || state == SDLLM_STATE_FULL) return st;
   if (!row_stride_ok(s.q_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
-  // the selection's last stage writes the index set and gathers the retained K/V rows into the cache
-  if (c.k_total > 0 && (!aligned16(k_cache) || !aligned16(v_cache) || !row_stride_ok(s.cache_stride, s.head_dim)))
-    return SDLLM_ERR_INVALID_ARG;
-  const GatherArgs gather{k_in, v_in, k_cache, v_cache};
-  return score_select_impl(s, q_blk, k_in, idx, nullptr, nullptr, ws, w.base, (hipStream_t)stream,
-                           w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts, c.k_total > 0 ? &gather : nullptr);
+  st = score_select_impl(s, q_blk, k_in, idx, nullptr, nullptr, ws, w.base, (hipStream_t)stream,
+                         w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts);
+  if (st != SDLLM_OK) return st;
+  return sdllm_compact_kv(shape, k_in, v_in, idx, k_cache, v_cache, stream);
 }
 
 int32_t sdllm_dense_attn(const sdllm_shape_t* shape, const void* q_full, const int64_t* q_full_stride,

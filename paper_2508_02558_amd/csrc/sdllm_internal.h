@@ -103,10 +103,7 @@ struct ScoreParams {
 
 struct SelectParams {
   const float* score;   // [rows, n_cand]
-  float* pooled;        // optional [rows, n_cand]: the pooled scores as floats (only when the caller wants them)
-  uint32_t* keys;       // [rows, n_cand] workspace: order-preserving integer image of the pooled scores
-  uint32_t* thr;        // [rows, 2, 2] workspace: per ranked segment {threshold key, equal entries to keep}
-  uint32_t* bins;       // workspace of select_bins_words() words (segments too long for one workgroup), else null
+  float* pooled;        // optional [rows, n_cand]: the pooled scores (only when the caller wants them)
   int32_t* idx;         // [rows, k_total]
   int32_t rows;         // B * Hkv
   int32_t n_cand;
@@ -119,16 +116,15 @@ struct SelectParams {
   // candidates appended unconditionally after the ranked ones (prefix-only eviction keeps the
   // whole suffix): candidate indices [tail_begin, tail_begin + tail_len)
   int32_t tail_begin, tail_len, tail_out;
-  int32_t parts;        // set by the launcher: pooling workgroups per segment (long segments)
-  // gather of the retained rows, fused into the emission (k == null: indices only)
-  const void* k;
-  const void* v;
-  void* kc;
-  void* vc;
-  int64_t s_sb, s_sh, s_sr;  // source strides in BYTES
-  int64_t c_sb, c_sh, c_sr;  // cache strides in BYTES
-  int32_t hkv, row_bytes;
+  // workspace of the path for segments too long for one workgroup (sizes: select_workspace()), else null
+  uint32_t* keys;       // [rows, n_cand] order-preserving integer image of the pooled scores
+  uint32_t* thr;        // [rows, 2, 2] per ranked segment {threshold key, equal entries to keep}
+  uint32_t* bins;       // [rows, 2, parts] lists of non-empty histogram bins
+  uint32_t* offs;       // [rows, 2, chunks, 2] entries above / equal to the threshold before each 1024 candidates
+  int32_t parts, chunks;   // set by the launcher
 };
+
+struct SelectWorkspace { size_t keys, thr, bins, offs; };   // in 32-bit words
 
 struct CompactParams {
   const void* k;
@@ -166,7 +162,7 @@ hipError_t launch_score_mfma_bf16(const ScoreParams& p, hipStream_t s);
 bool score_mfma_supports_group(int group);
 hipError_t launch_score_simple(const ScoreParams& p, int dtype, hipStream_t s);
 hipError_t launch_select(const SelectParams& p, hipStream_t s);
-size_t select_bins_words(const SelectParams& p);
+SelectWorkspace select_workspace(const SelectParams& p);
 hipError_t launch_compact(const CompactParams& p, hipStream_t s);
 hipError_t launch_dense_full_mfma_bf16(const DenseFullParams& p, hipStream_t s);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
