@@ -243,8 +243,8 @@ struct ScorePlan {
   int n_part, tiles_per_part, waves;
   // workspace: scores, softmax row statistics and, for segments too long for one workgroup, the selection's
   // key buffer, thresholds, bin lists and chunk offsets
-  size_t score_bytes, ml_bytes, keys_bytes, thr_bytes, bins_bytes, offs_bytes;
-  size_t ws_bytes() const { return score_bytes + ml_bytes + keys_bytes + thr_bytes + bins_bytes + offs_bytes; }
+  size_t score_bytes, ml_bytes, keys_bytes, sorted_bytes, bins_bytes;
+  size_t ws_bytes() const { return score_bytes + ml_bytes + keys_bytes + sorted_bytes + bins_bytes; }
 };
 
 // The ranked segments and the unconditional tail of the selection for this shape (Alg. 1 steps 8-10;
@@ -281,9 +281,8 @@ ScorePlan plan_score(const sdllm_shape_t& s) {
     fill_segments(s, c, q);
     const SelectWorkspace sw = select_workspace(q);
     pl.keys_bytes = align_up(sw.keys * sizeof(uint32_t));
-    pl.thr_bytes = align_up(sw.thr * sizeof(uint32_t));
+    pl.sorted_bytes = align_up(sw.sorted * sizeof(uint32_t));
     pl.bins_bytes = align_up(sw.bins * sizeof(uint32_t));
-    pl.offs_bytes = align_up(sw.offs * sizeof(uint32_t));
   }
   pl.mfma = s.dtype == SDLLM_BF16 && s.head_dim == 128 && s.block_len == 32 &&
             score_mfma_supports_group(s.n_q_heads / s.n_kv_heads) && seg_fits_u32(s.kv_stride[2], s.seq_len, 2);
@@ -332,11 +331,9 @@ int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void*
   at += pl.ml_bytes;
   uint32_t* keys = pl.keys_bytes ? (uint32_t*)at : nullptr;
   at += pl.keys_bytes;
-  uint32_t* thr = pl.thr_bytes ? (uint32_t*)at : nullptr;
-  at += pl.thr_bytes;
+  uint32_t* sorted = pl.sorted_bytes ? (uint32_t*)at : nullptr;
+  at += pl.sorted_bytes;
   uint32_t* bins = pl.bins_bytes ? (uint32_t*)at : nullptr;
-  at += pl.bins_bytes;
-  uint32_t* offs = pl.offs_bytes ? (uint32_t*)at : nullptr;
 
   ScoreParams sp{};
   sp.q = q_blk; sp.k = k_full;
@@ -361,7 +358,7 @@ int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void*
   SelectParams q{};
   fill_segments(s, c, q);
   q.score = score; q.pooled = pooled_out; q.idx = idx_out;
-  q.keys = keys; q.thr = thr; q.bins = bins; q.offs = offs;
+  q.keys = keys; q.sorted = sorted; q.bins = bins;
   e = launch_select(q, hs);
   return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
 }

@@ -117,14 +117,13 @@ struct SelectParams {
   // whole suffix): candidate indices [tail_begin, tail_begin + tail_len)
   int32_t tail_begin, tail_len, tail_out;
   // workspace of the path for segments too long for one workgroup (sizes: select_workspace()), else null
-  uint32_t* keys;       // [rows, n_cand] order-preserving integer image of the pooled scores
-  uint32_t* thr;        // [rows, 2, 2] per ranked segment {threshold key, equal entries to keep}
-  uint32_t* bins;       // [rows, 2, parts] lists of non-empty histogram bins
-  uint32_t* offs;       // [rows, 2, chunks, 2] entries above / equal to the threshold before each 1024 candidates
-  int32_t parts, chunks;   // set by the launcher
+  uint32_t* keys;       // [rows, n_cand] order-preserving integer image of the pooled scores, in position order
+  uint32_t* sorted;     // [rows, n_cand] the same keys, every chunk of 1024 ordered by leading bits
+  uint32_t* bins;       // [rows, 2, chunks] lists of the non-empty leading-bit bins of every chunk
+  int32_t chunks;       // set by the launcher: chunks of the longest ranked segment
 };
 
-struct SelectWorkspace { size_t keys, thr, bins, offs; };   // in 32-bit words
+struct SelectWorkspace { size_t keys, sorted, bins; };   // in 32-bit words
 
 struct CompactParams {
   const void* k;
@@ -163,6 +162,7 @@ bool score_mfma_supports_group(int group);
 hipError_t launch_score_simple(const ScoreParams& p, int dtype, hipStream_t s);
 hipError_t launch_select(const SelectParams& p, hipStream_t s);
 SelectWorkspace select_workspace(const SelectParams& p);
+int select_max_segment();
 hipError_t launch_compact(const CompactParams& p, hipStream_t s);
 hipError_t launch_dense_full_mfma_bf16(const DenseFullParams& p, hipStream_t s);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);

@@ -15,14 +15,14 @@
 // in registers (select_kernel: the score row is read from memory exactly once; four 8-bit radix passes
 // with LDS histograms; emission by counting every (chunk, wave) cell, one scan of the cell counts, then
 // the writes).
-// Longer segments are spread over the machine in three launches:
-//   select_pool_kernel     one workgroup per 2048 candidates: pooling, keys to a key buffer, and a compact
-//                          list of the non-empty bins of the keys' leading 12 bits;
-//   select_resolve_kernel  one workgroup per segment: adds the lists up, finds the bin that holds the k-th
-//                          value, collects that bin's members (a few hundred keys as a rule) and resolves
-//                          the remaining 20 bits on them alone; then one sweep over the keys leaves, per
-//                          1024 candidates, how many entries above and equal to T precede them;
-//   select_emit_kernel     one workgroup per 1024 candidates: position-ordered emission from those counts.
+// Longer segments (up to 1M candidates) are spread over the machine in two launches:
+//   select_pool_kernel    one workgroup per 2048 candidates: pooling, keys to a key buffer, and per chunk of
+//                         1024 candidates the list of the non-empty bins of the keys' leading 12 bits plus the
+//                         chunk's keys ordered by bin;
+//   select_finish_kernel  one workgroup per 4096 candidates: finds the segment's threshold from the lists and
+//                         the members of the one bin that holds the k-th value (every workgroup of a segment
+//                         does this for itself, side by side), counts what precedes its own candidates and
+//                         emits them in position order.
 #include "sdllm_internal.h"
 
 namespace sdllm {
@@ -40,16 +40,12 @@ constexpr int kSelRegItems = 8;                        // longest register-resid
 constexpr int kPoolChunks = 2;                         // chunks of 1024 candidates per select_pool_kernel workgroup
 constexpr int kPartLen = kPoolChunks * kSelThreads;
 constexpr int kBinShift = 20, kBins = 4096;            // leading 12 bits of a key
-constexpr int kBinListCap = kPartLen;                  // a part cannot occupy more bins than it has candidates
-static_assert(kBinListCap >= 256, "select_resolve_kernel reads the first 256 pairs of every list unconditionally");
+constexpr int kBinListCap = kSelThreads;               // a chunk cannot occupy more bins than it has candidates
 constexpr int kBinListStride = 1 + 2 * kBinListCap;    // words per list: count, then (bin, count) pairs
-constexpr int kSweep = 32;                            // keys a thread of select_resolve_kernel loads per trip to memory
-constexpr int kMemberCap = 8192;                       // members of the threshold bin held in LDS by select_resolve_kernel
-constexpr int kEmitThreads = 256;
-constexpr int kEmitWaves = kEmitThreads / 64;
-constexpr int kEmitItems = 4;
-constexpr int kEmitChunk = kEmitThreads * kEmitItems;  // candidates per select_emit_kernel workgroup
-static_assert(kEmitChunk == kSelThreads, "select_resolve_kernel counts per chunk of kSelThreads candidates");
+static_assert(kBinListCap >= 128, "select_finish_kernel reads the first 128 pairs of every list unconditionally");
+constexpr int kMemberCap = 6144;                       // members of the threshold bin held in LDS by select_finish_kernel
+constexpr int kFinishChunks = 4;                       // chunks of 1024 candidates one select_finish_kernel workgroup emits
+constexpr int kMaxChunks = 1024;                       // chunks per segment the long-segment path handles (1M candidates)
 
 __device__ __forceinline__ uint32_t order_key(float v) {
   const uint32_t u = __float_as_uint(v);
@@ -217,14 +213,6 @@ __device__ __forceinline__ void pool_chunks(const float* score, int len, int it0
   }
 }
 
-// The pair the emission of a long segment reads per (row, ranked segment): threshold key and number of
-// equal keys to keep.  "keep everything" is (0, len): every key is above or equal to 0; "keep nothing"
-// is (max, 0).
-__device__ __forceinline__ void publish_threshold(uint32_t* thr, int row, int seg, uint32_t key, uint32_t need_eq) {
-  thr[(row * 2 + seg) * 2] = key;
-  thr[(row * 2 + seg) * 2 + 1] = need_eq;
-}
-
 // Exclusive scan, in place, of the n_cells (<= 1024) per-cell counts of the emission pass; cell
 // it*16 + wave is the 64 candidates wave `wave` holds in chunk `it`, so index order is position order.
 // Two workgroup barriers inside; the caller synchronises before (counts written) and may read after.
@@ -357,11 +345,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   }
 }
 
-// ------------------------------------------------------------------ stage 1 of long segments, one workgroup per 2048 candidates
+// ------------------------------------------------------------------ long segments, launch 1: pooling and bucketing
+// One workgroup per two chunks of 1024 candidates.  Besides the keys in position order (key buffer) it
+// leaves, per chunk, the list of the non-empty bins of the keys' leading 12 bits with their counts, and
+// the chunk's keys once more ordered by bin (a counting sort through the chunk's histogram; the order
+// inside a bin is arbitrary), so that the second launch can pick the members of any one bin out of a
+// chunk without looking at the chunk's other keys.
 template <int HALF>
 __global__ __launch_bounds__(kSelThreads) void select_pool_kernel(const SelectParams p) {
-  __shared__ uint32_t hist[kBins];
-  __shared__ uint32_t wave_cnt[kSelWaves];
+  __shared__ uint32_t hist[kPoolChunks][kBins];
+  __shared__ uint32_t wave_n[kPoolChunks][kSelWaves], wave_s[kPoolChunks][kSelWaves];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -377,6 +370,7 @@ __global__ __launch_bounds__(kSelThreads) void select_pool_kernel(const SelectPa
   const float* score = p.score + (size_t)row * p.n_cand + begin;
   float* pooled = p.pooled ? p.pooled + (size_t)row * p.n_cand + begin : nullptr;
   uint32_t* key_out = p.keys + (size_t)row * p.n_cand + begin;
+  uint32_t* sorted = p.sorted + (size_t)row * p.n_cand + begin;
 
   const int half = p.pool_half;
   const float inv_s = 1.f / (float)(2 * half + 1);
@@ -401,51 +395,67 @@ __global__ __launch_bounds__(kSelThreads) void select_pool_kernel(const SelectPa
       if (pooled) pooled[c] = pv[u];
     }
   }
-  if (k <= 0 || k >= len) return;   // nothing to rank: stage 2 publishes keep-nothing / keep-everything
+  if (k <= 0 || k >= len) return;   // nothing to rank: everything or nothing is kept
 
-  // histogram of the keys' leading bits, then the list of its non-empty bins
-  for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
+  for (int i = tid; i < kPoolChunks * kBins; i += kSelThreads) (&hist[0][0])[i] = 0;
   __syncthreads();
-  BinRun run;
 #pragma unroll
-  for (int u = 0; u < kPoolChunks; ++u) run_add(hist, run, c_first + u * kSelThreads + tid < len, keys[u] >> kBinShift);
-  run_flush(hist, run, lane);
+  for (int u = 0; u < kPoolChunks; ++u)
+    if (c_first + u * kSelThreads + tid < len) atomicAdd(&hist[u][keys[u] >> kBinShift], 1u);
   __syncthreads();
-  uint32_t h[4];
-  uint32_t n = 0;
+  // thread t owns bins 4t .. 4t+3 of both chunks: number of non-empty bins and of keys before them
+  uint32_t h[kPoolChunks][4], n[kPoolChunks], sum[kPoolChunks], n_incl[kPoolChunks], s_incl[kPoolChunks];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    h[j] = hist[4 * tid + j];
-    n += h[j] != 0;
-  }
-  uint32_t incl = n;   // inclusive prefix sum over the lanes of this wave
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t t = __shfl_up(incl, o);
-    if (lane >= o) incl += t;
-  }
-  if (lane == 63) wave_cnt[wave] = incl;
-  __syncthreads();
-  uint32_t at = incl - n;
+  for (int u = 0; u < kPoolChunks; ++u) {
+    n[u] = sum[u] = 0;
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w)
-    if (w < wave) at += wave_cnt[w];
-  uint32_t* list = p.bins + ((size_t)(row * 2 + seg) * p.parts + part) * kBinListStride;
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-    if (h[j] != 0) {   // at most kPartLen non-empty bins, so at < kBinListCap
-      list[1 + 2 * at] = 4 * tid + j;
-      list[2 + 2 * at] = h[j];
-      ++at;
+    for (int j = 0; j < 4; ++j) {
+      h[u][j] = hist[u][4 * tid + j];
+      n[u] += h[u][j] != 0;
+      sum[u] += h[u][j];
     }
-  if (tid == kSelThreads - 1) list[0] = at;
+    n_incl[u] = n[u];
+    s_incl[u] = sum[u];
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t tn = __shfl_up(n_incl[u], o), ts = __shfl_up(s_incl[u], o);
+      if (lane >= o) { n_incl[u] += tn; s_incl[u] += ts; }
+    }
+    if (lane == 63) { wave_n[u][wave] = n_incl[u]; wave_s[u][wave] = s_incl[u]; }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < kPoolChunks; ++u) {
+    const int chunk = part * kPoolChunks + u;
+    if ((int64_t)chunk * kSelThreads >= len) break;   // workgroup-uniform
+    uint32_t at = n_incl[u] - n[u], start = s_incl[u] - sum[u];
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w)
+      if (w < wave) { at += wave_n[u][w]; start += wave_s[u][w]; }
+    uint32_t* list = p.bins + ((size_t)(row * 2 + seg) * p.chunks + chunk) * kBinListStride;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      hist[u][4 * tid + j] = start;   // from here on: where the bin's next key goes in the sorted chunk
+      start += h[u][j];
+      if (h[u][j] != 0) {             // at most 1024 non-empty bins per chunk, so at < kBinListCap
+        list[1 + 2 * at] = 4 * tid + j;
+        list[2 + 2 * at] = h[u][j];
+        ++at;
+      }
+    }
+    if (tid == kSelThreads - 1) list[0] = at;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < kPoolChunks; ++u) {
+    const int c = c_first + u * kSelThreads + tid;
+    if (c < len) {
+      const uint32_t at = atomicAdd(&hist[u][keys[u] >> kBinShift], 1u);   // < number of keys of the chunk
+      sorted[(size_t)(part * kPoolChunks + u) * kSelThreads + at] = keys[u];
+    }
+  }
 }
 
-// ------------------------------------------------------------------ stage 2 of long segments, one workgroup per segment
-// One workgroup is one CU: a sweep over all keys of a 32k-candidate segment is bound by instruction issue
-// (sixteen waves on four SIMDs), so the two sweeps below spend a handful of instructions per 64 keys: no
-// bounds checks in full sweeps, counts taken from wave-wide compares (the popcount is scalar work), one LDS
-// atomic per wave and sweep (members) or none at all (chunk counts).
-
+// ------------------------------------------------------------------ long segments, launch 2: threshold and emission
 // The bin that holds the `remaining`-th largest key of a 1024-bin histogram and the number of keys in
 // higher bins, by all 1024 threads (one bin each).  One workgroup barrier inside; the caller synchronises
 // before (histogram complete) and after.
@@ -466,44 +476,64 @@ __device__ __forceinline__ void pick_bin_1024(const uint32_t* h, uint32_t remain
   if (above < remaining && remaining <= above + mine) { *s_bin = tid; *s_above = above; }
 }
 
-// This thread's keys of one sweep: element c0 + u*1024 + tid, u < kSweep (zero past the end).
-__device__ __forceinline__ void load_sweep(const uint32_t* keys, int c0, int len, int tid, bool full, uint32_t (&key)[kSweep]) {
-  if (full) {
-#pragma unroll
-    for (int u = 0; u < kSweep; ++u) key[u] = keys[c0 + u * kSelThreads + tid];
-  } else {
-#pragma unroll
-    for (int u = 0; u < kSweep; ++u) {
-      const int c = c0 + u * kSelThreads + tid;
-      key[u] = c < len ? keys[c] : 0u;
-    }
-  }
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(const SelectParams p) {
+// One workgroup emits kFinishChunks consecutive chunks of a segment (candidate c = chunk*1024 + tid).  Every
+// workgroup of a segment first finds the segment's threshold for itself, from what launch 1 left behind:
+// it adds the chunks' bin lists up (a few thousand pairs), finds the bin of the k-th value, fetches that
+// bin's members out of the bin-sorted chunks (a few hundred to a few thousand keys) and resolves their
+// remaining 20 bits; it then counts, again from lists and members only, the entries above and equal to
+// the threshold in the chunks before its own.  That work is the same for all workgroups of a segment, but
+// they run side by side on different CUs, which is faster than a launch boundary between a one-workgroup
+// threshold kernel and the emission (no kernel here ever walks all keys of a segment on one CU: 32k keys
+// cost one CU 6 us per sweep in instruction issue alone).
+// blockIdx.y >= n_seg is the unconditional tail (prefix-only eviction keeps the whole suffix).
+__global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const SelectParams p) {
   __shared__ uint32_t members[kMemberCap];
   __shared__ uint32_t hist[kBins];
   __shared__ uint32_t hist2[2][1024];
-  __shared__ uint32_t wave_tot[kSelWaves];
-  __shared__ uint32_t wave_gt[kSelWaves][kSweep], wave_eq[kSelWaves][kSweep];
+  __shared__ uint16_t chunk_above[kMaxChunks], chunk_below[kMaxChunks], chunk_mem[kMaxChunks];
+  __shared__ uint32_t wave_tot[kSelWaves], wave_gt[kSelWaves], wave_eq[kSelWaves], scan_gt[kSelWaves], scan_eq[kSelWaves];
+  __shared__ uint32_t cell_gt[kFinishChunks * kSelWaves], cell_eq[kFinishChunks * kSelWaves];
   __shared__ uint32_t s_bin, s_above, s_members;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int seg = blockIdx.x;
-  const int row = blockIdx.y;
-  const int len = p.seg_len[seg];
-  const int k = p.seg_k[seg];
-  if (len <= 0 || k <= 0) {
-    if (tid == 0) publish_threshold(p.thr, row, seg, 0xffffffffu, 0u);
+  const int sx = blockIdx.y;
+  const int row = blockIdx.z;
+  const bool tail = sx >= p.n_seg;
+  const int begin = tail ? p.tail_begin : p.seg_begin[sx];
+  const int len = tail ? p.tail_len : p.seg_len[sx];
+  const int out0 = tail ? p.tail_out : p.seg_out[sx];
+  const int k = tail ? len : p.seg_k[sx];
+  const int own0 = blockIdx.x * kFinishChunks;          // first own chunk
+  const int c_own = own0 * kSelThreads;
+  if (c_own >= len || k <= 0) return;
+  int32_t* out = p.idx + (size_t)row * p.k_total + out0;
+  if (k >= len) {   // everything is kept
+#pragma unroll
+    for (int it = 0; it < kFinishChunks; ++it) {
+      const int c = c_own + it * kSelThreads + tid;
+      if (c < len) out[c] = cand_pos(begin + c, p.block_off, p.block_len);
+    }
     return;
   }
-  if (k >= len) {
-    if (tid == 0) publish_threshold(p.thr, row, seg, 0u, (uint32_t)len);
-    return;
+  const uint32_t* keys = p.keys + (size_t)row * p.n_cand + begin;
+  const uint32_t* sorted = p.sorted + (size_t)row * p.n_cand + begin;
+  const uint32_t* lists = p.bins + (size_t)(row * 2 + sx) * p.chunks * kBinListStride;
+  const int n_chunks = (len + kSelThreads - 1) / kSelThreads;   // <= kMaxChunks (launcher)
+
+  // own keys: requested now, used at the very end
+  uint32_t own_key[kFinishChunks];
+#pragma unroll
+  for (int it = 0; it < kFinishChunks; ++it) {
+    const int c = c_own + it * kSelThreads + tid;
+    own_key[it] = c < len ? keys[c] : 0u;
   }
-  const uint32_t* keys = p.keys + (size_t)row * p.n_cand + p.seg_begin[seg];
 
   DBG_STAMP(0);
   for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
@@ -511,22 +541,21 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(const Selec
   if (tid == 0) s_members = 0;
   __syncthreads();
 
-  // add up the parts' bin lists: wave w takes parts w, w + 16, ...; the length of a list and its first
-  // 256 pairs are requested together (a list seldom has more), so a part costs one trip to memory
-  const int parts_used = (len + kPartLen - 1) / kPartLen;
-  for (int part = wave; part < parts_used; part += kSelWaves) {
-    const uint32_t* list = p.bins + ((size_t)(row * 2 + seg) * p.parts + part) * kBinListStride;
-    uint32_t bin[4], cnt[4];
+  // 1. the segment's histogram of leading bits: wave w adds up the lists of chunks w, w + 16, ...; the
+  //    length of a list and its first 128 pairs are requested together (a list seldom has more)
+  for (int c = wave; c < n_chunks; c += kSelWaves) {
+    const uint32_t* list = lists + (size_t)c * kBinListStride;
+    uint32_t bin[2], cnt[2];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {   // kBinListCap >= 256: always inside the list's allocation
+    for (int u = 0; u < 2; ++u) {   // inside the list's allocation whatever its length
       bin[u] = list[1 + 2 * (u * 64 + lane)];
       cnt[u] = list[2 + 2 * (u * 64 + lane)];
     }
     const int n = min((int)list[0], kBinListCap);
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < 2; ++u)
       if (u * 64 + lane < n) atomicAdd(&hist[bin[u] & (kBins - 1)], cnt[u]);
-    for (int i = 256 + lane; i < n; i += 64) atomicAdd(&hist[list[1 + 2 * i] & (kBins - 1)], list[2 + 2 * i]);
+    for (int i = 128 + lane; i < n; i += 64) atomicAdd(&hist[list[1 + 2 * i] & (kBins - 1)], list[2 + 2 * i]);
   }
   __syncthreads();
   DBG_STAMP(1);
@@ -538,36 +567,44 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(const Selec
   const bool listed = n_members <= (uint32_t)kMemberCap;
 
   DBG_STAMP(2);
-  // collect the members of the threshold bin (their order is irrelevant: only counts are taken from
-  // them); a bin with more members than the list holds is walked in the key buffer in every pass
-  if (listed) {
-    for (int c0 = 0; c0 < len; c0 += kSweep * kSelThreads) {
-      const bool full = c0 + kSweep * kSelThreads <= len;
-      uint32_t key[kSweep];
-      load_sweep(keys, c0, len, tid, full, key);
-      uint32_t wave_members = 0;
+  // 2. per chunk: keys in higher bins, keys in lower bins (= where the threshold bin's members start in
+  //    the bin-sorted chunk) and members; the members go to the LDS list
+  for (int c = wave; c < n_chunks; c += kSelWaves) {
+    const uint32_t* list = lists + (size_t)c * kBinListStride;
+    uint32_t bin[2], cnt[2];
 #pragma unroll
-      for (int u = 0; u < kSweep; ++u) {
-        const bool in = (key[u] >> kBinShift) == bin1 && (full || c0 + u * kSelThreads + tid < len);
-        wave_members += (uint32_t)__popcll(__ballot(in));
-      }
-      uint32_t at = 0;
-      if (lane == 0 && wave_members) at = atomicAdd(&s_members, wave_members);
-      at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
-#pragma unroll
-      for (int u = 0; u < kSweep; ++u) {
-        const bool in = (key[u] >> kBinShift) == bin1 && (full || c0 + u * kSelThreads + tid < len);
-        const uint64_t b = __ballot(in);
-        const uint32_t mine = at + (uint32_t)__popcll(b & ((1ull << lane) - 1ull));
-        if (in && mine < (uint32_t)kMemberCap) members[mine] = key[u];
-        at += (uint32_t)__popcll(b);
-      }
+    for (int u = 0; u < 2; ++u) {   // as in step 1: length and first 128 pairs in one trip
+      bin[u] = list[1 + 2 * (u * 64 + lane)];
+      cnt[u] = list[2 + 2 * (u * 64 + lane)];
     }
-    __syncthreads();
+    const int n = min((int)list[0], kBinListCap);
+    // keys above and below the threshold bin, at most 1024 each: packed 16 bits apiece they take one wave
+    // reduction; the members are the rest of the chunk
+    uint32_t packed = 0;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      if (u * 64 + lane < n) packed += bin[u] > bin1 ? cnt[u] : (bin[u] < bin1 ? cnt[u] << 16 : 0u);
+    for (int i = 128 + lane; i < n; i += 64) {
+      const uint32_t b = list[1 + 2 * i], ct = list[2 + 2 * i];
+      packed += b > bin1 ? ct : (b < bin1 ? ct << 16 : 0u);
+    }
+    packed = wave_sum(packed);
+    const uint32_t in_chunk = (uint32_t)min(kSelThreads, len - c * kSelThreads);
+    const uint32_t above = packed & 0xffffu, below = packed >> 16, mem = in_chunk - above - below;
+    if (lane == 0) { chunk_above[c] = (uint16_t)above; chunk_below[c] = (uint16_t)below; chunk_mem[c] = (uint16_t)mem; }
+    if (listed && mem) {
+      uint32_t at = 0;
+      if (lane == 0) at = atomicAdd(&s_members, mem);
+      at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+      for (uint32_t i = lane; i < mem; i += 64)
+        if (at + i < (uint32_t)kMemberCap) members[at + i] = sorted[(size_t)c * kSelThreads + below + i];
+    }
   }
+  __syncthreads();
 
   DBG_STAMP(3);
-  // the remaining 20 bits, MSB first, in two digits of 10 bits
+  // 3. the remaining 20 bits of the threshold, MSB first, in two digits of 10 bits; a bin with more members
+  //    than the list holds is read from the bin-sorted chunks in both passes
   uint32_t prefix = bin1 << kBinShift, mask = 0xffffffffu << kBinShift;
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
@@ -579,12 +616,12 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(const Selec
         run_add(hist2[pass], run, (key & mask) == prefix, (key >> shift) & 1023u);
       }
     } else {
-      for (int c0 = 0; c0 < len; c0 += kSweep * kSelThreads) {
-        uint32_t key[kSweep];
-        load_sweep(keys, c0, len, tid, false, key);
-#pragma unroll
-        for (int u = 0; u < kSweep; ++u)
-          run_add(hist2[pass], run, c0 + u * kSelThreads + tid < len && (key[u] & mask) == prefix, (key[u] >> shift) & 1023u);
+      for (int c = wave; c < n_chunks; c += kSelWaves) {
+        const uint32_t below = chunk_below[c], mem = chunk_mem[c];
+        for (uint32_t i = lane; i < mem; i += 64) {
+          const uint32_t key = sorted[(size_t)c * kSelThreads + below + i];
+          run_add(hist2[pass], run, (key & mask) == prefix, (key >> shift) & 1023u);
+        }
       }
     }
     run_flush(hist2[pass], run, lane);
@@ -595,127 +632,52 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(const Selec
     mask |= 1023u << shift;
     remaining -= s_above;
   }
-  if (tid == 0) publish_threshold(p.thr, row, seg, prefix, remaining);
+  const uint32_t thr = prefix;
+  const uint32_t need_eq = remaining;
 
   DBG_STAMP(4);
-  // For the emission: per chunk of 1024 candidates, the number of entries above / equal to the threshold
-  // before it.  Chunk u of a sweep is element u of every thread: every wave counts its 64 entries of each
-  // chunk with two wave-wide compares, lane u keeps the counts of chunk u, and wave 0 adds the sixteen
-  // waves' counts up, scans them over the sweep's chunks and writes the offsets.
-  const uint32_t thr = prefix;
-  uint32_t* offs = p.offs + (size_t)(row * 2 + seg) * p.chunks * 2;
-  uint32_t base_gt = 0, base_eq = 0;   // running totals (wave 0)
-  for (int c0 = 0; c0 < len; c0 += kSweep * kSelThreads) {
-    const bool full = c0 + kSweep * kSelThreads <= len;
-    uint32_t key[kSweep];
-    load_sweep(keys, c0, len, tid, full, key);
-    uint32_t my_gt = 0, my_eq = 0;
-#pragma unroll
-    for (int u = 0; u < kSweep; ++u) {
-      const bool in = full || c0 + u * kSelThreads + tid < len;
-      const uint32_t g = (uint32_t)__popcll(__ballot(in && key[u] > thr)), e = (uint32_t)__popcll(__ballot(in && key[u] == thr));
-      if (lane == u) { my_gt = g; my_eq = e; }
+  // 4. entries above / equal to the threshold in the chunks before this workgroup's own
+  uint32_t gt_b = 0, eq_b = 0;
+  for (int c = wave; c < own0; c += kSelWaves) {
+    const uint32_t below = chunk_below[c], mem = chunk_mem[c];
+    if (lane == 0) gt_b += chunk_above[c];
+    for (uint32_t i = lane; i < mem; i += 64) {
+      const uint32_t key = sorted[(size_t)c * kSelThreads + below + i];
+      gt_b += key > thr;
+      eq_b += key == thr;
     }
-    __syncthreads();   // wave 0 has read the previous sweep's counts
-    if (lane < kSweep) { wave_gt[wave][lane] = my_gt; wave_eq[wave][lane] = my_eq; }
-    __syncthreads();
-    if (wave == 0) {
-      uint32_t g = 0, e = 0;
-      if (lane < kSweep) {
+  }
+  gt_b = wave_sum(gt_b);
+  eq_b = wave_sum(eq_b);
+  if (lane == 0) { wave_gt[wave] = gt_b; wave_eq[wave] = eq_b; }
+
+  // 5. own candidates: cell (it, wave) = 64 consecutive candidates; cells in index order are in position order
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  uint32_t my_gt = 0, my_eq = 0;   // lane `it` keeps the counts of cell (it, wave)
 #pragma unroll
-        for (int w = 0; w < kSelWaves; ++w) { g += wave_gt[w][lane]; e += wave_eq[w][lane]; }
-      }
-      uint32_t sg = g, se = e;   // inclusive scan over the sweep's chunks
-      for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t tg = __shfl_up(sg, o), te = __shfl_up(se, o);
-        if (lane >= o) { sg += tg; se += te; }
-      }
-      const int chunk = c0 / kSelThreads + lane;
-      if (lane < kSweep && chunk < p.chunks && (int64_t)chunk * kSelThreads < len) {
-        offs[2 * chunk] = base_gt + sg - g;
-        offs[2 * chunk + 1] = base_eq + se - e;
-      }
-      base_gt += (uint32_t)__builtin_amdgcn_readlane((int)sg, 63);
-      base_eq += (uint32_t)__builtin_amdgcn_readlane((int)se, 63);
-    }
+  for (int it = 0; it < kFinishChunks; ++it) {
+    const bool valid = c_own + it * kSelThreads + tid < len;
+    const uint64_t b_gt = __ballot(valid && own_key[it] > thr), b_eq = __ballot(valid && own_key[it] == thr);
+    if (lane == it) { my_gt = __popcll(b_gt); my_eq = __popcll(b_eq); }
+  }
+  if (lane < kFinishChunks) { cell_gt[lane * kSelWaves + wave] = my_gt; cell_eq[lane * kSelWaves + wave] = my_eq; }
+  __syncthreads();
+  gt_b = eq_b = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) { gt_b += wave_gt[w]; eq_b += wave_eq[w]; }
+  scan_cells(cell_gt, cell_eq, kFinishChunks * kSelWaves, scan_gt, scan_eq, tid, lane, wave);
+#pragma unroll
+  for (int it = 0; it < kFinishChunks; ++it) {
+    const int c = c_own + it * kSelThreads + tid;
+    const bool gt = c < len && own_key[it] > thr;
+    const bool eq = c < len && own_key[it] == thr;
+    const uint64_t b_gt = __ballot(gt), b_eq = __ballot(eq);
+    const uint32_t gt_before = gt_b + cell_gt[it * kSelWaves + wave] + __popcll(b_gt & lt_mask);
+    const uint32_t eq_before = eq_b + cell_eq[it * kSelWaves + wave] + __popcll(b_eq & lt_mask);
+    if (gt) out[gt_before + min(eq_before, need_eq)] = cand_pos(begin + c, p.block_off, p.block_len);
+    else if (eq && eq_before < need_eq) out[gt_before + eq_before] = cand_pos(begin + c, p.block_off, p.block_len);
   }
   DBG_STAMP(5);
-}
-
-// ------------------------------------------------------------------ stage 3 of long segments: position-ordered emission
-// One workgroup per kEmitChunk consecutive candidates of a segment; candidate c = chunk*1024 + it*256 + tid.
-// blockIdx.y >= n_seg is the unconditional tail (prefix-only eviction keeps the whole suffix).
-__global__ __launch_bounds__(kEmitThreads) void select_emit_kernel(const SelectParams p) {
-  __shared__ uint32_t cell_gt[kEmitItems * kEmitWaves], cell_eq[kEmitItems * kEmitWaves];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int chunk = blockIdx.x;
-  const int sx = blockIdx.y;
-  const int row = blockIdx.z;
-  const bool tail = sx >= p.n_seg;
-  const int begin = tail ? p.tail_begin : p.seg_begin[sx];
-  const int len = tail ? p.tail_len : p.seg_len[sx];
-  const int out0 = tail ? p.tail_out : p.seg_out[sx];
-  const int c0 = chunk * kEmitChunk;
-  if (c0 >= len) return;
-  int32_t* idx_row = p.idx + (size_t)row * p.k_total + out0;
-  if (tail) {
-#pragma unroll
-    for (int it = 0; it < kEmitItems; ++it) {
-      const int c = c0 + it * kEmitThreads + tid;
-      if (c < len) idx_row[c] = cand_pos(begin + c, p.block_off, p.block_len);
-    }
-    return;
-  }
-  const uint32_t thr = p.thr[(row * 2 + sx) * 2];
-  const uint32_t need = p.thr[(row * 2 + sx) * 2 + 1];
-  const uint32_t* offs = p.offs + ((size_t)(row * 2 + sx) * p.chunks + chunk) * 2;
-  // keep-everything / keep-nothing segments have no counts on file: both follow from the chunk's position
-  const bool ranked = p.seg_k[sx] > 0 && p.seg_k[sx] < len;
-  const uint32_t gt_b = ranked ? offs[0] : 0u;
-  const uint32_t eq_b = ranked ? offs[1] : (uint32_t)c0;
-  const uint32_t* keys = p.keys + (size_t)row * p.n_cand + begin;
-
-  // cell (it, wave) = 64 consecutive candidates; cells in index order are in position order
-  bool gt[kEmitItems], eq[kEmitItems];
-  uint64_t b_gt[kEmitItems], b_eq[kEmitItems];
-  uint32_t key[kEmitItems];
-#pragma unroll
-  for (int it = 0; it < kEmitItems; ++it) {
-    const int c = c0 + it * kEmitThreads + tid;
-    key[it] = c < len ? keys[c] : 0u;
-  }
-#pragma unroll
-  for (int it = 0; it < kEmitItems; ++it) {
-    const bool valid = c0 + it * kEmitThreads + tid < len;
-    gt[it] = valid && key[it] > thr;
-    eq[it] = valid && key[it] == thr;
-    b_gt[it] = __ballot(gt[it]);
-    b_eq[it] = __ballot(eq[it]);
-    if (lane == 0) {
-      cell_gt[it * kEmitWaves + wave] = (uint32_t)__popcll(b_gt[it]);
-      cell_eq[it * kEmitWaves + wave] = (uint32_t)__popcll(b_eq[it]);
-    }
-  }
-  __syncthreads();
-  uint32_t cg[kEmitItems * kEmitWaves], ce[kEmitItems * kEmitWaves];
-#pragma unroll
-  for (int j = 0; j < kEmitItems * kEmitWaves; ++j) { cg[j] = cell_gt[j]; ce[j] = cell_eq[j]; }
-  const uint64_t lt_mask = (1ull << lane) - 1ull;
-#pragma unroll
-  for (int it = 0; it < kEmitItems; ++it) {
-    uint32_t og = 0, oe = 0;
-#pragma unroll
-    for (int j = 0; j < kEmitItems * kEmitWaves; ++j)
-      if (j < it * kEmitWaves + wave) { og += cg[j]; oe += ce[j]; }
-    const uint32_t gt_before = gt_b + og + (uint32_t)__popcll(b_gt[it] & lt_mask);
-    const uint32_t eq_before = eq_b + oe + (uint32_t)__popcll(b_eq[it] & lt_mask);
-    const int pos = cand_pos(begin + c0 + it * kEmitThreads + tid, p.block_off, p.block_len);
-    if (gt[it]) idx_row[gt_before + min(eq_before, need)] = pos;
-    else if (eq[it] && eq_before < need) idx_row[gt_before + eq_before] = pos;
-  }
 }
 
 // ------------------------------------------------------------------ launchers
@@ -725,20 +687,21 @@ static int longest_ranked(const SelectParams& p) {
   return longest;
 }
 
-// Workspace of the long-segment path, in 32-bit words: key buffer, thresholds, bin lists, chunk offsets
-// (all zero when every ranked segment fits one workgroup).
+// Workspace of the long-segment path, in 32-bit words: keys in position order, keys sorted by bin per chunk,
+// per-chunk bin lists (all zero when every ranked segment fits one workgroup).
 SelectWorkspace select_workspace(const SelectParams& p) {
   SelectWorkspace w{};
   const int longest = longest_ranked(p);
   if (longest <= kSelRegItems * kSelThreads) return w;
-  const size_t parts = (size_t)(longest + kPartLen - 1) / kPartLen;
-  const size_t chunks = (size_t)(longest + kEmitChunk - 1) / kEmitChunk;
+  const size_t chunks = (size_t)(longest + kSelThreads - 1) / kSelThreads;
   w.keys = (size_t)p.rows * p.n_cand;
-  w.thr = (size_t)p.rows * 4;
-  w.bins = (size_t)p.rows * 2 * parts * kBinListStride;
-  w.offs = (size_t)p.rows * 2 * chunks * 2;
+  w.sorted = (size_t)p.rows * p.n_cand;
+  w.bins = (size_t)p.rows * 2 * chunks * kBinListStride;
   return w;
 }
+
+// Longest ranked segment the selection handles (beyond it the per-chunk tables of select_finish_kernel overflow).
+int select_max_segment() { return kMaxChunks * kSelThreads; }
 
 template <int ITEMS>
 static void launch_items(const SelectParams& p, dim3 grid, hipStream_t s) {
@@ -771,20 +734,18 @@ hipError_t launch_select(const SelectParams& q, hipStream_t s) {
   else if (longest <= 4 * kSelThreads) launch_items<4>(p, grid, s);
   else if (longest <= kSelRegItems * kSelThreads) launch_items<kSelRegItems>(p, grid, s);
   else {
-    if (!p.keys || !p.thr || !p.bins || !p.offs) return hipErrorInvalidValue;
-    p.parts = (longest + kPartLen - 1) / kPartLen;
-    p.chunks = (longest + kEmitChunk - 1) / kEmitChunk;
-    const dim3 pgrid(p.parts, p.n_seg, p.rows), block(kSelThreads);
+    if (!p.keys || !p.sorted || !p.bins || longest > select_max_segment()) return hipErrorInvalidValue;
+    p.chunks = (longest + kSelThreads - 1) / kSelThreads;
+    const dim3 pgrid((longest + kPartLen - 1) / kPartLen, p.n_seg, p.rows), block(kSelThreads);
     switch (p.pool_half) {
       case 0: hipLaunchKernelGGL(select_pool_kernel<0>, pgrid, block, 0, s, p); break;
       case 1: hipLaunchKernelGGL(select_pool_kernel<1>, pgrid, block, 0, s, p); break;
       case 2: hipLaunchKernelGGL(select_pool_kernel<2>, pgrid, block, 0, s, p); break;
       default: hipLaunchKernelGGL(select_pool_kernel<-1>, pgrid, block, 0, s, p); break;
     }
-    hipLaunchKernelGGL(select_resolve_kernel, dim3(p.n_seg, p.rows), block, 0, s, p);
     const int longest_any = p.tail_len > longest ? p.tail_len : longest;
-    if (p.k_total > 0)
-      hipLaunchKernelGGL(select_emit_kernel, dim3((longest_any + kEmitChunk - 1) / kEmitChunk, nx, p.rows), dim3(kEmitThreads), 0, s, p);
+    const int per_wg = kFinishChunks * kSelThreads;
+    if (p.k_total > 0) hipLaunchKernelGGL(select_finish_kernel, dim3((longest_any + per_wg - 1) / per_wg, nx, p.rows), block, 0, s, p);
   }
   return hipGetLastError();
 }
