@@ -542,20 +542,39 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
   __syncthreads();
 
   // 1. the segment's histogram of leading bits: wave w adds up the lists of chunks w, w + 16, ...; the
-  //    length of a list and its first 128 pairs are requested together (a list seldom has more)
-  for (int c = wave; c < n_chunks; c += kSelWaves) {
-    const uint32_t* list = lists + (size_t)c * kBinListStride;
-    uint32_t bin[2], cnt[2];
+  //    length of a list and its first 128 pairs are requested together (a list seldom has more), and
+  //    those of a wave's first two chunks stay in registers for step 2
+  constexpr int kHeld = 2;
+  uint32_t held_bin[kHeld][2], held_cnt[kHeld][2];
+  int held_n[kHeld];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {   // inside the list's allocation whatever its length
-      bin[u] = list[1 + 2 * (u * 64 + lane)];
-      cnt[u] = list[2 + 2 * (u * 64 + lane)];
+  for (int j = 0; j < kHeld; ++j) {
+    const int c = wave + j * kSelWaves;
+    held_n[j] = 0;
+    if (c < n_chunks) {   // wave-uniform
+      const uint32_t* list = lists + (size_t)c * kBinListStride;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {   // inside the list's allocation whatever its length
+        held_bin[j][u] = list[1 + 2 * (u * 64 + lane)];
+        held_cnt[j][u] = list[2 + 2 * (u * 64 + lane)];
+      }
+      held_n[j] = min((int)list[0], kBinListCap);
     }
-    const int n = min((int)list[0], kBinListCap);
+  }
+#pragma unroll
+  for (int j = 0; j < kHeld; ++j) {
+    const int c = wave + j * kSelWaves;
+    if (c >= n_chunks) break;
+    const uint32_t* list = lists + (size_t)c * kBinListStride;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
-      if (u * 64 + lane < n) atomicAdd(&hist[bin[u] & (kBins - 1)], cnt[u]);
-    for (int i = 128 + lane; i < n; i += 64) atomicAdd(&hist[list[1 + 2 * i] & (kBins - 1)], list[2 + 2 * i]);
+      if (u * 64 + lane < held_n[j]) atomicAdd(&hist[held_bin[j][u] & (kBins - 1)], held_cnt[j][u]);
+    for (int i = 128 + lane; i < held_n[j]; i += 64) atomicAdd(&hist[list[1 + 2 * i] & (kBins - 1)], list[2 + 2 * i]);
+  }
+  for (int c = wave + kHeld * kSelWaves; c < n_chunks; c += kSelWaves) {
+    const uint32_t* list = lists + (size_t)c * kBinListStride;
+    const int n = min((int)list[0], kBinListCap);
+    for (int i = lane; i < n; i += 64) atomicAdd(&hist[list[1 + 2 * i] & (kBins - 1)], list[2 + 2 * i]);
   }
   __syncthreads();
   DBG_STAMP(1);
@@ -568,26 +587,11 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
 
   DBG_STAMP(2);
   // 2. per chunk: keys in higher bins, keys in lower bins (= where the threshold bin's members start in
-  //    the bin-sorted chunk) and members; the members go to the LDS list
-  for (int c = wave; c < n_chunks; c += kSelWaves) {
-    const uint32_t* list = lists + (size_t)c * kBinListStride;
-    uint32_t bin[2], cnt[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {   // as in step 1: length and first 128 pairs in one trip
-      bin[u] = list[1 + 2 * (u * 64 + lane)];
-      cnt[u] = list[2 + 2 * (u * 64 + lane)];
-    }
-    const int n = min((int)list[0], kBinListCap);
-    // keys above and below the threshold bin, at most 1024 each: packed 16 bits apiece they take one wave
-    // reduction; the members are the rest of the chunk
-    uint32_t packed = 0;
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-      if (u * 64 + lane < n) packed += bin[u] > bin1 ? cnt[u] : (bin[u] < bin1 ? cnt[u] << 16 : 0u);
-    for (int i = 128 + lane; i < n; i += 64) {
-      const uint32_t b = list[1 + 2 * i], ct = list[2 + 2 * i];
-      packed += b > bin1 ? ct : (b < bin1 ? ct << 16 : 0u);
-    }
+  //    the bin-sorted chunk) and members; the members go to the LDS list.  Keys above and below the
+  //    threshold bin are at most 1024 each: packed 16 bits apiece they take one wave reduction, and the
+  //    members are the rest of the chunk.
+  auto side = [&](uint32_t b, uint32_t ct) { return b > bin1 ? ct : (b < bin1 ? ct << 16 : 0u); };
+  auto finish_chunk = [&](int c, uint32_t packed) {
     packed = wave_sum(packed);
     const uint32_t in_chunk = (uint32_t)min(kSelThreads, len - c * kSelThreads);
     const uint32_t above = packed & 0xffffu, below = packed >> 16, mem = in_chunk - above - below;
@@ -599,6 +603,25 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
       for (uint32_t i = lane; i < mem; i += 64)
         if (at + i < (uint32_t)kMemberCap) members[at + i] = sorted[(size_t)c * kSelThreads + below + i];
     }
+  };
+#pragma unroll
+  for (int j = 0; j < kHeld; ++j) {
+    const int c = wave + j * kSelWaves;
+    if (c >= n_chunks) break;
+    const uint32_t* list = lists + (size_t)c * kBinListStride;
+    uint32_t packed = 0;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      if (u * 64 + lane < held_n[j]) packed += side(held_bin[j][u], held_cnt[j][u]);
+    for (int i = 128 + lane; i < held_n[j]; i += 64) packed += side(list[1 + 2 * i], list[2 + 2 * i]);
+    finish_chunk(c, packed);
+  }
+  for (int c = wave + kHeld * kSelWaves; c < n_chunks; c += kSelWaves) {
+    const uint32_t* list = lists + (size_t)c * kBinListStride;
+    const int n = min((int)list[0], kBinListCap);
+    uint32_t packed = 0;
+    for (int i = lane; i < n; i += 64) packed += side(list[1 + 2 * i], list[2 + 2 * i]);
+    finish_chunk(c, packed);
   }
   __syncthreads();
 
@@ -609,13 +632,13 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
     const int shift = pass == 0 ? 10 : 0;
-    BinRun run;
-    if (listed) {
+    if (listed) {   // a few keys per thread, spread over 1024 bins: one LDS atomic each
       for (uint32_t i = tid; i < n_members; i += kSelThreads) {
         const uint32_t key = members[i];
-        run_add(hist2[pass], run, (key & mask) == prefix, (key >> shift) & 1023u);
+        if ((key & mask) == prefix) atomicAdd(&hist2[pass][(key >> shift) & 1023u], 1u);
       }
     } else {
+      BinRun run;
       for (int c = wave; c < n_chunks; c += kSelWaves) {
         const uint32_t below = chunk_below[c], mem = chunk_mem[c];
         for (uint32_t i = lane; i < mem; i += 64) {
@@ -623,8 +646,8 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
           run_add(hist2[pass], run, (key & mask) == prefix, (key >> shift) & 1023u);
         }
       }
+      run_flush(hist2[pass], run, lane);
     }
-    run_flush(hist2[pass], run, lane);
     __syncthreads();
     pick_bin_1024(hist2[pass], remaining, tid, lane, wave, wave_tot, &s_bin, &s_above);
     __syncthreads();
