@@ -154,13 +154,14 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
     const int heads = s.batch * s.n_q_heads;
     // Split the keys of a head over workgroups only while the grid is small: as many splits as keep
     // the grid within one workgroup per CU (an eight-wave workgroup fills a CU's LDS, so workgroup
-    // number 257 waits for a whole round: 56 heads x 4 splits 15.1 us, x 5 splits 22.3 us), at most 6
-    // (8 from 256 tiles per head on: 28 heads x 261 tiles, 20.4 us with 6 splits, 19.0 us with 8),
-    // and a minimum of tiles per workgroup (below).  Batch-1 shapes are pure latency and a wave with
+    // number 257 waits for a whole round: 56 heads x 4 splits 15.1 us, x 5 splits 22.3 us), at most 8
+    // (28 heads, replayed as a HIP graph so that only GPU time counts: 69 tiles 12.6 us with 6 splits and
+    // 12.15 us with 8, 137 tiles 16.85 -> 15.2 us, 261 tiles 20.3 -> 18.5 us), and a minimum of tiles per
+    // workgroup (below).  Batch-1 shapes are pure latency and a wave with
     // one or two tiles beats a longer chain (28/4 heads x 4352 keys: 17.2 -> 15.0 us with 6 or 7 splits
     // instead of 4).  From 129 heads on there is one workgroup per head.
     int n_split = kNumCUs / heads;
-    const int most = tiles >= 256 ? 8 : 6;
+    const int most = 8;
     if (n_split > most) n_split = most;
     // A split costs fp32 partials and a second launch of about 4 us: with up to 32 heads (where three or
     // more splits fit) seven tiles per workgroup repay it, one tile per wave or two (32 heads x 21 tiles,
