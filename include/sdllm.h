@@ -137,6 +137,8 @@ int32_t sdllm_cache_state(int32_t step_in_block, int32_t delay, int32_t* state);
  *   pooled_out optional [B,Hkv,N] fp32 contiguous, candidate-indexed (c < o -> position c,
  *              c >= o -> position c + b): the pooled score.  May be NULL.
  *   score_out  optional [B,Hkv,N] fp32: the score before pooling.  May be NULL.
+ * A ranked segment (prefix, suffix, or the joint array) of more than 1 048 576 candidates returns
+ * SDLLM_ERR_UNSUPPORTED.
  *   ws         workspace of at least sdllm_workspace_bytes(SDLLM_OP_SCORE_SELECT) bytes,
  *              256-byte aligned; contents undefined afterwards.
  */

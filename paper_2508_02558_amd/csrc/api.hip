@@ -324,6 +324,12 @@ int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void*
   const ScorePlan pl = plan_score(s);
   if (!ws || ws_bytes < pl.ws_bytes() || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return SDLLM_ERR_WORKSPACE;
   if (c.n_cand == 0) return SDLLM_OK;
+  {
+    SelectParams probe{};
+    fill_segments(s, c, probe);
+    for (int i = 0; i < probe.n_seg; ++i)
+      if (probe.seg_len[i] > select_max_segment()) return SDLLM_ERR_UNSUPPORTED;   // beyond the selection's per-segment tables
+  }
 
   char* at = (char*)ws;
   float* score = score_out ? score_out : (float*)at;

@@ -152,6 +152,18 @@ def test_static_scratch_is_visible_in_the_device_image(lib, tmp_path):
     assert rows and all(r[4] == "GLOBAL" and int(r[2]) == B.SDLLM_STATIC_SCRATCH_BYTES for r in rows), syms
 
 
+def test_segments_beyond_the_selection_limit_are_rejected_before_any_launch(lib):
+    # a prefix of more than 1M candidates: the selection's per-chunk tables end there
+    s = B.make_shape(batch=1, n_q_heads=1, n_kv_heads=1, head_dim=128, seq_len=1_200_000 + 32, block_off=1_200_000, block_len=32,
+                     dtype=B.SDLLM_BF16)
+    fake = ctypes.c_void_p(0x1000)
+    z = ctypes.c_void_p(None)
+    assert lib.sdllm_score_select(ctypes.byref(s), fake, fake, fake, z, z, fake, 1 << 40, z) == B.SDLLM_ERR_UNSUPPORTED
+    ok = B.make_shape(batch=1, n_q_heads=1, n_kv_heads=1, head_dim=128, seq_len=1_000_000 + 32, block_off=1_000_000, block_len=32,
+                      dtype=B.SDLLM_BF16)
+    assert B.sdllm_workspace_bytes(ok, B.SDLLM_OP_SCORE_SELECT) > 3 * 4 * 1_000_000   # scores + two key buffers
+
+
 def test_workspace_sizes(lib):
     s = _shape()
     for op in (B.SDLLM_OP_SCORE_SELECT, B.SDLLM_OP_COMPACT_KV, B.SDLLM_OP_SPARSE_ATTN, B.SDLLM_OP_BLOCK_STEP):
