@@ -305,6 +305,30 @@ def test_exact_ties_across_workgroup_boundaries(prompt, modes):
     assert (idx0 == np.concatenate(want)[None, None]).all()
 
 
+@pytest.mark.parametrize("prompt,gen,batch", [
+    (9217, 9248, 1),     # prefix 9 chunks + 1 candidate, suffix exactly 9 chunks: both segments take the two-launch path
+    (8193, 64, 3),       # one candidate beyond the single-workgroup limit; short suffix; several rows
+    (16384, 12320, 2),   # prefix exactly 16 chunks (two per wave of the finish kernel), suffix 12 chunks + 32
+])
+def test_select_with_both_segments_long(prompt, gen, batch):
+    # chunk counts that are odd, even, and one over a boundary, on both sides of the block at once
+    _note(f"[case] both segments long: prompt={prompt} gen={gen} batch={batch}")
+    w = wl.WORKLOADS["llada8b_layer"].scaled(batch=batch, n_q_heads=2, n_kv_heads=2, prompt=prompt, gen=gen, retention=0.4)
+    inp = wl.make_block_inputs(w, 0, 0, 2, device=DEV)
+    shape = U.shape_for(w, 0)
+    gl = U.GpuLayer(shape, DEV)
+    q = inp["q"][1].contiguous()
+    idx_gpu, pooled, _ = gl.score_select(q, inp["k_full"])
+    idx_orc, pooled_orc, _ = U.oracle_score_select(shape, q, inp["k_full"])
+    np.testing.assert_allclose(pooled.cpu().double().numpy(), pooled_orc, rtol=3e-5, atol=1e-12)
+    ties = 0
+    for bi in range(batch):
+        for g in range(w.n_kv_heads):
+            ties += U.compare_index_rows(idx_gpu[bi, g], idx_orc[bi, g], pooled_orc[bi, g], w.seq_len, inp["block_off"], w.block,
+                                         U.ranked_segments(shape))
+    _note(f"[done] ties in band: {ties}")
+
+
 def test_scores_match_oracle_values():
     _note("[case] score / pooled values")
     # every group size has its own instantiation of the two scoring passes (the stand-alone entry
