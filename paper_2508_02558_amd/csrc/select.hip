@@ -70,6 +70,47 @@ __device__ __forceinline__ float pool_at(const float* score, int c, int len, int
   return v + 0.f;   // -0 -> +0 so that equal values have equal keys
 }
 
+// Whole-wave shifts by one lane as DPP moves (no LDS traffic, unlike a general shuffle):
+// shr: lane i takes v[i-1], lane 0 takes `fill`; shl: lane i takes v[i+1], lane 63 takes `fill`.
+__device__ __forceinline__ float wave_shr1(float v, float fill) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, fill), __builtin_bit_cast(int, v),
+                                                               0x138, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float wave_shl1(float v, float fill) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, fill), __builtin_bit_cast(int, v),
+                                                               0x130, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float lane_value(float v, int src_lane) {   // src_lane: compile-time constant
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src_lane));
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves only (six vector
+// instructions; a shuffle-based scan is six dependent trips through the LDS crossbar): four shifts inside
+// each row of 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.
+// A lane whose source lies outside its row, or whose row is masked out, adds zero.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_add(uint32_t v) {
+  return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
+}
+__device__ __forceinline__ uint32_t wave_scan_incl(uint32_t v) {
+  v = dpp_add<0x111, 0xF>(v);   // row_shr:1
+  v = dpp_add<0x112, 0xF>(v);   // row_shr:2
+  v = dpp_add<0x114, 0xF>(v);   // row_shr:4
+  v = dpp_add<0x118, 0xF>(v);   // row_shr:8
+  v = dpp_add<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+  v = dpp_add<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+  return v;
+}
+// Sum over the wave (the same value in every lane, scalar).
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)wave_scan_incl(v), 63);
+}
+// Inclusive suffix sum: lane i gets v[i] + v[i+1] + ... + v[63].
+__device__ __forceinline__ uint32_t wave_scan_suffix_incl(uint32_t v) {
+  const uint32_t pre = wave_scan_incl(v);
+  return (uint32_t)__builtin_amdgcn_readlane((int)pre, 63) - pre + v;
+}
+
 // Histogram building.  A thread walks its keys and counts runs of equal bins in registers (pooled
 // softmax scores share their leading bits, so in the first pass a thread's whole walk is usually one
 // run); a run ends with one LDS atomic.  The last run of every lane is flushed together: when all
@@ -98,26 +139,11 @@ __device__ __forceinline__ void run_flush(uint32_t* hist, const BinRun& r, int l
   const uint32_t lead_bin = (uint32_t)__builtin_amdgcn_readlane((int)r.bin, leader);
   const uint64_t same = __ballot(active && r.bin == lead_bin);
   if (same == act) {
-    uint32_t total = r.count;   // 0 in idle lanes
-    for (int o = 32; o > 0; o >>= 1) total += __shfl_xor(total, o);
+    const uint32_t total = wave_sum(r.count);   // 0 in idle lanes
     if (lane == leader) atomicAdd(&hist[lead_bin], total);
   } else if (active) {
     atomicAdd(&hist[r.bin], r.count);
   }
-}
-
-// Whole-wave shifts by one lane as DPP moves (no LDS traffic, unlike a general shuffle):
-// shr: lane i takes v[i-1], lane 0 takes `fill`; shl: lane i takes v[i+1], lane 63 takes `fill`.
-__device__ __forceinline__ float wave_shr1(float v, float fill) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, fill), __builtin_bit_cast(int, v),
-                                                               0x138, 0xF, 0xF, false));
-}
-__device__ __forceinline__ float wave_shl1(float v, float fill) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, fill), __builtin_bit_cast(int, v),
-                                                               0x130, 0xF, 0xF, false));
-}
-__device__ __forceinline__ float lane_value(float v, int src_lane) {   // src_lane: compile-time constant
-  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src_lane));
 }
 
 // Wave 0, after a pass's 256-bin histogram is complete: the bin that holds the `remaining`-th largest
@@ -125,11 +151,7 @@ __device__ __forceinline__ float lane_value(float v, int src_lane) {   // src_la
 __device__ __forceinline__ void pick_bin(const uint32_t* h, uint32_t remaining, int lane, uint32_t* s_bin, uint32_t* s_above) {
   const uint32_t h0 = h[4 * lane], h1 = h[4 * lane + 1], h2 = h[4 * lane + 2], h3 = h[4 * lane + 3];
   const uint32_t lane_sum = h0 + h1 + h2 + h3;
-  uint32_t suf = lane_sum;   // inclusive suffix sum over lanes
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t t = __shfl_down(suf, o);
-    if (lane + o < 64) suf += t;
-  }
+  const uint32_t suf = wave_scan_suffix_incl(lane_sum);
   const uint32_t a3 = suf - lane_sum, a2 = a3 + h3, a1 = a2 + h2, a0 = a1 + h1;
   if (a3 < remaining && remaining <= a3 + h3) { *s_bin = 4 * lane + 3; *s_above = a3; }
   if (a2 < remaining && remaining <= a2 + h2) { *s_bin = 4 * lane + 2; *s_above = a2; }
@@ -143,11 +165,7 @@ __device__ __forceinline__ void pick_bin_wide(const uint32_t* h, uint32_t remain
                                               uint32_t* wave_tot, uint32_t* s_bin, uint32_t* s_above) {
   const uint32_t h0 = h[4 * tid], h1 = h[4 * tid + 1], h2 = h[4 * tid + 2], h3 = h[4 * tid + 3];
   const uint32_t mine = h0 + h1 + h2 + h3;
-  uint32_t suf = mine;   // inclusive suffix sum over the lanes of this wave
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t t = __shfl_down(suf, o);
-    if (lane + o < 64) suf += t;
-  }
+  const uint32_t suf = wave_scan_suffix_incl(mine);   // over the lanes of this wave
   if (lane == 0) wave_tot[wave] = suf;
   __syncthreads();
   uint32_t above_waves = 0;
@@ -219,11 +237,7 @@ __device__ __forceinline__ void pool_chunks(const float* score, int len, int it0
 __device__ __forceinline__ void scan_cells(uint32_t* cell_gt, uint32_t* cell_eq, int n_cells, uint32_t* wave_gt, uint32_t* wave_eq,
                                            int tid, int lane, int wave) {
   const uint32_t g = tid < n_cells ? cell_gt[tid] : 0u, e = tid < n_cells ? cell_eq[tid] : 0u;
-  uint32_t sg = g, se = e;
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t tg = __shfl_up(sg, o), te = __shfl_up(se, o);
-    if (lane >= o) { sg += tg; se += te; }
-  }
+  const uint32_t sg = wave_scan_incl(g), se = wave_scan_incl(e);
   if (lane == 63) { wave_gt[wave] = sg; wave_eq[wave] = se; }
   __syncthreads();
   uint32_t og = 0, oe = 0;
@@ -265,6 +279,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   float* pooled = p.pooled ? p.pooled + (size_t)row * p.n_cand + begin : nullptr;
   int32_t* out = idx_row + p.seg_out[seg];
 
+  DBG_STAMP(8);
   // 1. pooling
   const int half = p.pool_half;
   const float inv_s = 1.f / (float)(2 * half + 1);
@@ -288,6 +303,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
       if (pooled) pooled[c] = pv[it];
     }
   }
+  DBG_STAMP(9);
   if (k <= 0) return;
   if (k >= len) {
     for (int c = tid; c < len; c += kSelThreads) out[c] = cand_pos(begin + c, p.block_off, p.block_len);
@@ -316,6 +332,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     mask |= 255u << shift;
     remaining -= s_above;
   }
+  DBG_STAMP(10);
   const uint32_t thr = prefix;
   const uint32_t need_eq = remaining;
 
@@ -331,6 +348,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   }
   if (lane < ITEMS) { cell_gt[lane * kSelWaves + wave] = my_gt; cell_eq[lane * kSelWaves + wave] = my_eq; }
   __syncthreads();
+  DBG_STAMP(11);
   scan_cells(cell_gt, cell_eq, kCells, wave_gt, wave_eq, tid, lane, wave);
 #pragma unroll
   for (int it = 0; it < ITEMS; ++it) {
@@ -343,6 +361,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     if (gt) out[gt_before + min(eq_before, need_eq)] = cand_pos(begin + c, p.block_off, p.block_len);
     else if (eq && eq_before < need_eq) out[gt_before + eq_before] = cand_pos(begin + c, p.block_off, p.block_len);
   }
+  DBG_STAMP(12);
 }
 
 // ------------------------------------------------------------------ long segments, launch 1: pooling and bucketing
@@ -414,12 +433,8 @@ __global__ __launch_bounds__(kSelThreads) void select_pool_kernel(const SelectPa
       n[u] += h[u][j] != 0;
       sum[u] += h[u][j];
     }
-    n_incl[u] = n[u];
-    s_incl[u] = sum[u];
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t tn = __shfl_up(n_incl[u], o), ts = __shfl_up(s_incl[u], o);
-      if (lane >= o) { n_incl[u] += tn; s_incl[u] += ts; }
-    }
+    n_incl[u] = wave_scan_incl(n[u]);
+    s_incl[u] = wave_scan_incl(sum[u]);
     if (lane == 63) { wave_n[u][wave] = n_incl[u]; wave_s[u][wave] = s_incl[u]; }
   }
   __syncthreads();
@@ -462,11 +477,7 @@ __global__ __launch_bounds__(kSelThreads) void select_pool_kernel(const SelectPa
 __device__ __forceinline__ void pick_bin_1024(const uint32_t* h, uint32_t remaining, int tid, int lane, int wave,
                                               uint32_t* wave_tot, uint32_t* s_bin, uint32_t* s_above) {
   const uint32_t mine = h[tid];
-  uint32_t suf = mine;   // inclusive suffix sum over the lanes of this wave
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t t = __shfl_down(suf, o);
-    if (lane + o < 64) suf += t;
-  }
+  const uint32_t suf = wave_scan_suffix_incl(mine);   // over the lanes of this wave
   if (lane == 0) wave_tot[wave] = suf;
   __syncthreads();
   uint32_t above = suf - mine;
@@ -474,11 +485,6 @@ __device__ __forceinline__ void pick_bin_1024(const uint32_t* h, uint32_t remain
   for (int w = 0; w < kSelWaves; ++w)
     if (w > wave) above += wave_tot[w];
   if (above < remaining && remaining <= above + mine) { *s_bin = tid; *s_above = above; }
-}
-
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
 }
 
 // One workgroup emits kFinishChunks consecutive chunks of a segment (candidate c = chunk*1024 + tid).  Every
