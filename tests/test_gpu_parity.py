@@ -329,6 +329,24 @@ def test_select_with_both_segments_long(prompt, gen, batch):
     _note(f"[done] ties in band: {ties}")
 
 
+def test_select_at_the_longest_supported_segment():
+    # a prefix of 1 046 528 candidates = 1022 chunks, just under the two-launch path's limit of 1024: the
+    # per-chunk tables of the finish kernel are nearly full and every one of its 256 workgroups adds up
+    # 1022 bin lists
+    _note("[case] 1M-candidate segment")
+    w = wl.WORKLOADS["dream_long"].scaled(n_q_heads=1, n_kv_heads=1, prompt=1022 * 1024, gen=64, retention=0.1, sink=16)
+    inp = wl.make_block_inputs(w, n_steps=2, device=DEV)
+    shape = U.shape_for(w)
+    gl = U.GpuLayer(shape, DEV)
+    q = inp["q"][1].contiguous()
+    idx, _, score = gl.score_select(q, inp["k_full"])
+    idx_orc, pooled_orc, score_orc = U.oracle_score_select(shape, q, inp["k_full"])
+    np.testing.assert_allclose(score.cpu().double().numpy(), score_orc, rtol=1e-4, atol=1e-14)
+    ties = U.compare_index_rows(idx[0, 0], idx_orc[0, 0], pooled_orc[0, 0], w.seq_len, inp["block_off"], w.block,
+                                U.ranked_segments(shape))
+    _note(f"[done] ties in band: {ties}")
+
+
 def test_scores_match_oracle_values():
     _note("[case] score / pooled values")
     # every group size has its own instantiation of the two scoring passes (the stand-alone entry
