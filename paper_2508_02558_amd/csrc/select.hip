@@ -27,13 +27,6 @@
 
 namespace sdllm {
 
-#ifdef SDLLM_TUNING   // development builds only: timestamps of one workgroup's phases
-__device__ unsigned long long g_dbg[32];
-#define DBG_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) g_dbg[i] = wall_clock64(); } while (0)
-#else
-#define DBG_STAMP(i) do { } while (0)
-#endif
-
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelRegItems = 8;                        // longest register-resident variant (chunks of 1024)
@@ -279,7 +272,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   float* pooled = p.pooled ? p.pooled + (size_t)row * p.n_cand + begin : nullptr;
   int32_t* out = idx_row + p.seg_out[seg];
 
-  DBG_STAMP(8);
   // 1. pooling
   const int half = p.pool_half;
   const float inv_s = 1.f / (float)(2 * half + 1);
@@ -303,7 +295,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
       if (pooled) pooled[c] = pv[it];
     }
   }
-  DBG_STAMP(9);
   if (k <= 0) return;
   if (k >= len) {
     for (int c = tid; c < len; c += kSelThreads) out[c] = cand_pos(begin + c, p.block_off, p.block_len);
@@ -332,7 +323,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     mask |= 255u << shift;
     remaining -= s_above;
   }
-  DBG_STAMP(10);
   const uint32_t thr = prefix;
   const uint32_t need_eq = remaining;
 
@@ -348,7 +338,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   }
   if (lane < ITEMS) { cell_gt[lane * kSelWaves + wave] = my_gt; cell_eq[lane * kSelWaves + wave] = my_eq; }
   __syncthreads();
-  DBG_STAMP(11);
   scan_cells(cell_gt, cell_eq, kCells, wave_gt, wave_eq, tid, lane, wave);
 #pragma unroll
   for (int it = 0; it < ITEMS; ++it) {
@@ -361,7 +350,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     if (gt) out[gt_before + min(eq_before, need_eq)] = cand_pos(begin + c, p.block_off, p.block_len);
     else if (eq && eq_before < need_eq) out[gt_before + eq_before] = cand_pos(begin + c, p.block_off, p.block_len);
   }
-  DBG_STAMP(12);
 }
 
 // ------------------------------------------------------------------ long segments, launch 1: pooling and bucketing
@@ -541,7 +529,6 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
     own_key[it] = c < len ? keys[c] : 0u;
   }
 
-  DBG_STAMP(0);
   for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
   for (int i = tid; i < 2 * 1024; i += kSelThreads) (&hist2[0][0])[i] = 0;
   if (tid == 0) s_members = 0;
@@ -583,7 +570,6 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
     for (int i = lane; i < n; i += 64) atomicAdd(&hist[list[1 + 2 * i] & (kBins - 1)], list[2 + 2 * i]);
   }
   __syncthreads();
-  DBG_STAMP(1);
   pick_bin_wide(hist, (uint32_t)k, tid, lane, wave, wave_tot, &s_bin, &s_above);
   __syncthreads();
   const uint32_t bin1 = s_bin;
@@ -591,7 +577,6 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
   const uint32_t n_members = hist[bin1];
   const bool listed = n_members <= (uint32_t)kMemberCap;
 
-  DBG_STAMP(2);
   // 2. per chunk: keys in higher bins, keys in lower bins (= where the threshold bin's members start in
   //    the bin-sorted chunk) and members; the members go to the LDS list.  Keys above and below the
   //    threshold bin are at most 1024 each: packed 16 bits apiece they take one wave reduction, and the
@@ -631,7 +616,6 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
   }
   __syncthreads();
 
-  DBG_STAMP(3);
   // 3. the remaining 20 bits of the threshold, MSB first, in two digits of 10 bits; a bin with more members
   //    than the list holds is read from the bin-sorted chunks in both passes
   uint32_t prefix = bin1 << kBinShift, mask = 0xffffffffu << kBinShift;
@@ -664,7 +648,6 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
   const uint32_t thr = prefix;
   const uint32_t need_eq = remaining;
 
-  DBG_STAMP(4);
   // 4. entries above / equal to the threshold in the chunks before this workgroup's own
   uint32_t gt_b = 0, eq_b = 0;
   for (int c = wave; c < own0; c += kSelWaves) {
@@ -706,7 +689,6 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(const Select
     if (gt) out[gt_before + min(eq_before, need_eq)] = cand_pos(begin + c, p.block_off, p.block_len);
     else if (eq && eq_before < need_eq) out[gt_before + eq_before] = cand_pos(begin + c, p.block_off, p.block_len);
   }
-  DBG_STAMP(5);
 }
 
 // ------------------------------------------------------------------ launchers
@@ -778,9 +760,5 @@ hipError_t launch_select(const SelectParams& q, hipStream_t s) {
   }
   return hipGetLastError();
 }
-
-#ifdef SDLLM_TUNING
-extern "C" int sdllm_debug_stamps(unsigned long long* out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg), sizeof(g_dbg)); }
-#endif
 
 }  // namespace sdllm

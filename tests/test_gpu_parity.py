@@ -500,11 +500,12 @@ def test_fused_row_statistics_ignore_dominant_block_keys():
         _check_selected_rows(gl, shape, w, q, k_full, o, b, rows)
 
 
-def test_block_step_replays_identically_from_a_hip_graph():
+@pytest.mark.parametrize("prompt", [700, 9300])   # selection in one workgroup per segment / in two launches
+def test_block_step_replays_identically_from_a_hip_graph(prompt):
     # the library only enqueues kernels (no allocation, no memset, no host sync), so a block step can
     # be captured; every replay must reproduce the eager result, with eager work in between
-    _note("[case] HIP graph capture / replay")
-    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=8, n_kv_heads=8, prompt=700, gen=96)
+    _note(f"[case] HIP graph capture / replay, prompt {prompt}")
+    w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=8, n_kv_heads=8, prompt=prompt, gen=96)
     inp = wl.make_block_inputs(w, n_steps=3, device=DEV)
     shape = U.shape_for(w)
     gl = U.GpuLayer(shape, DEV)

@@ -38,3 +38,32 @@ def _random_case(seed):
 def test_random_shape_block(seed):
     w, block_index, modes = _random_case(seed)
     _run_block(w, layer=seed, block_index=block_index, n_steps=3, **modes)
+
+
+def _random_long_case(seed):
+    """Shapes whose ranked segments take the two-launch selection (more than 8192 candidates): a long prompt,
+    sometimes a long suffix as well, a block anywhere in the generation, every ranking variant."""
+    rng = np.random.default_rng(9000 + seed)
+    group = int(rng.choice([1, 2, 7]))
+    prompt = int(rng.integers(8193, 45000))
+    gen_blocks = int(rng.choice([2, 3, 300, 400]))          # the long generations give a long suffix too
+    w = wl.WORKLOADS["llada8b_layer"].scaled(
+        batch=int(rng.integers(1, 3)), n_q_heads=group, n_kv_heads=1, prompt=prompt, gen=32 * gen_blocks,
+        retention=float(rng.choice([0.05, 0.25, 0.5, 0.8])), pool_kernel=int(rng.choice([1, 3, 3, 5, 9])))
+    block_index = int(rng.integers(0, min(gen_blocks, 40)))
+    modes = {}
+    if rng.random() < 0.3:
+        modes.update(select_mode=B.SDLLM_JOINT, k_rounding=B.SDLLM_FLOOR)
+    if rng.random() < 0.3:
+        modes.update(score_mode=B.SDLLM_LOGIT_MEAN)
+    if rng.random() < 0.2:
+        modes.update(pool_mode=B.SDLLM_AVG_POOL)
+    if rng.random() < 0.2 and "select_mode" not in modes:
+        modes.update(evict_scope=B.SDLLM_EVICT_PREFIX_ONLY)
+    return w, block_index, modes
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_long_segment_block(seed):
+    w, block_index, modes = _random_long_case(seed)
+    _run_block(w, layer=seed, block_index=block_index, n_steps=3, **modes)
