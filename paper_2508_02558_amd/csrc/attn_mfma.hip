@@ -16,6 +16,8 @@
 //   * up to 8 waves per workgroup (the planner picks 4 or 5 for unsplit MHA heads) split the keys of
 //     one head and merge their running (max, sum, numerator) through LDS; more workgroups per head
 //     (split-KV) write fp32 partials that a small combine kernel merges.
+#include <type_traits>
+
 #include "attn_tile_math.h"
 
 namespace sdllm {
@@ -193,49 +195,70 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     p.cand_ml[slot * 64 + lane] = mc;
     p.cand_ml[slot * 64 + 32 + lane] = lc;
   }
-  float f_w[kMaxWavesPerWg];
-  float m_tot = -INFINITY, l_all = 0.f;
-  {
-    float m_w[kMaxWavesPerWg], l_w[kMaxWavesPerWg];
+  // With the wave count a compile-time constant every LDS read of the merge (the waves' (max, sum) and the
+  // up to ceil(16 / NW) slots this wave reduces) is requested before the first is used: one LDS round trip
+  // instead of one per slot.
+  auto merge = [&](auto nw_tag) {
+    constexpr int NW = decltype(nw_tag)::value;
+    constexpr int NJ = (16 + NW - 1) / NW;
+    float m_w[NW], l_w[NW], f_w[NW];
+    f32x4 part[NJ][NW];
 #pragma unroll
-    for (int w = 0; w < kMaxWavesPerWg; ++w) {
+    for (int w = 0; w < NW; ++w) {
       const float* ml = reinterpret_cast<const float*>(smem + w * kWaveLds + 64 * kRowBytes);
-      m_w[w] = w < nw ? ml[col] : -INFINITY;
-      l_w[w] = w < nw ? ml[32 + col] : 0.f;
+      m_w[w] = ml[col];
+      l_w[w] = ml[32 + col];
     }
 #pragma unroll
-    for (int w = 0; w < kMaxWavesPerWg; ++w) m_tot = fmaxf(m_tot, m_w[w]);
+    for (int j = 0; j < NJ; ++j) {
+      const int i = min(wave + j * NW, 15);   // past the last slot (some waves, last round): re-read slot 15, not stored
 #pragma unroll
-    for (int w = 0; w < kMaxWavesPerWg; ++w) {
+      for (int w = 0; w < NW; ++w)
+        part[j][w] = *reinterpret_cast<const f32x4*>(smem + w * kWaveLds + lane * kRowBytes + i * 16);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float m_tot = -INFINITY, l_all = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) m_tot = fmaxf(m_tot, m_w[w]);
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
       // a wave that saw no tile parked (-inf, 0, 0): factor 0
       f_w[w] = m_w[w] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_w[w] - m_tot);
       l_all += f_w[w] * l_w[w];
     }
-  }
-  const float inv = 1.f / l_all;
-  for (int i = wave; i < 16; i += nw) {
-    f32x4 part[kMaxWavesPerWg];
+    const float inv = 1.f / l_all;
 #pragma unroll
-    for (int w = 0; w < kMaxWavesPerWg; ++w)
-      part[w] = w < nw ? *reinterpret_cast<const f32x4*>(smem + w * kWaveLds + lane * kRowBytes + i * 16)
-                       : f32x4{0.f, 0.f, 0.f, 0.f};
-    f32x4 o4 = {0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NJ; ++j) {
+      const int i = wave + j * NW;
+      if (i < 16) {
+        f32x4 o4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int w = 0; w < kMaxWavesPerWg; ++w) o4 += part[w] * f_w[w];
-    const int d0 = out_col0(i >> 2, i & 3, half);   // slot i = (e, i4): four consecutive output columns
-    if (p.n_split == 1) {
-      bf16x4 ob;
+        for (int w = 0; w < NW; ++w) o4 += part[j][w] * f_w[w];
+        const int d0 = out_col0(i >> 2, i & 3, half);   // slot i = (e, i4): four consecutive output columns
+        if (p.n_split == 1) {
+          bf16x4 ob;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ob[r] = (__bf16)(o4[r] * inv);
-      char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
-      *reinterpret_cast<bf16x4*>(op + d0 * 2) = ob;
-    } else {
-      *reinterpret_cast<f32x4*>(p.part_o + (slot * 32 + col) * 128 + d0) = o4;
+          for (int r = 0; r < 4; ++r) ob[r] = (__bf16)(o4[r] * inv);
+          char* op = (char*)p.out + 2 * (b * p.o_sb + h * p.o_sh + col * p.o_sr);
+          *reinterpret_cast<bf16x4*>(op + d0 * 2) = ob;
+        } else {
+          *reinterpret_cast<f32x4*>(p.part_o + (slot * 32 + col) * 128 + d0) = o4;
+        }
+      }
     }
-  }
-  if (p.n_split > 1 && wave == 0 && lane < 32) {
-    p.part_ml[slot * 64 + lane] = m_tot;
-    p.part_ml[slot * 64 + 32 + lane] = l_all;
+    if (p.n_split > 1 && wave == 0 && lane < 32) {
+      p.part_ml[slot * 64 + lane] = m_tot;
+      p.part_ml[slot * 64 + 32 + lane] = l_all;
+    }
+  };
+  switch (nw) {
+    case 2: merge(std::integral_constant<int, 2>{}); break;
+    case 3: merge(std::integral_constant<int, 3>{}); break;
+    case 4: merge(std::integral_constant<int, 4>{}); break;
+    case 5: merge(std::integral_constant<int, 5>{}); break;
+    case 6: merge(std::integral_constant<int, 6>{}); break;
+    case 7: merge(std::integral_constant<int, 7>{}); break;
+    default: merge(std::integral_constant<int, 8>{}); break;
   }
 }
 

@@ -57,6 +57,12 @@ def _run_block(w, layer=0, block_index=0, n_steps=4, delay=1, **modes):
                 want_v = torch.gather(v_full, 2, ig[..., None].expand(-1, -1, -1, w.head_dim))
                 assert torch.equal(gl.k_cache[:, :, :gl.k_total], want_k)
                 assert torch.equal(gl.v_cache[:, :, :gl.k_total], want_v)
+                # ... and equals the oracle's gather of the same rows (Sec. 3.3, fourth equation), value for value:
+                # a bf16 or fp32 element is exactly representable in the oracle's float64
+                for bi in range(w.batch):
+                    kc, vc = orc.compact_kv(wl.to_f64(k_full[bi]), wl.to_f64(v_full[bi]), idx_gpu[bi])
+                    assert np.array_equal(wl.to_f64(gl.k_cache[bi, :, :gl.k_total]), kc), f"K_c batch {bi}"
+                    assert np.array_equal(wl.to_f64(gl.v_cache[bi, :, :gl.k_total]), vc), f"V_c batch {bi}"
                 cache_gpu = (want_k, want_v)
         else:
             kb, vb = kb_all[t].contiguous(), vb_all[t].contiguous()
