@@ -207,8 +207,12 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
 
 // cand_ml != null (dense MFMA launches only): also emit the scoring pass's row statistics over the
 // candidate keys, n_split partials per query row.
+// deferred != null: when the keys are split over workgroups, leave the merge of the splits to the caller
+// (it gets the launch parameters in *deferred and must run launch_compact_combine or launch_attn_combine on
+// the same stream before the partials' workspace is reused); deferred->n_split == 1 says nothing is left.
 int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, const KvSegment& b, void* out, void* ws,
-                 size_t ws_bytes, hipStream_t stream, float* cand_ml = nullptr, int cand0_end = 0, int cand1_begin = 0) {
+                 size_t ws_bytes, hipStream_t stream, float* cand_ml = nullptr, int cand0_end = 0, int cand1_begin = 0,
+                 AttnParams* deferred = nullptr) {
   const AttnPlan pl = plan_attn(s, a.n, a.sr, b.n, b.sr);
   if (pl.ws_bytes() > 0 && (!ws || ws_bytes < pl.ws_bytes())) return SDLLM_ERR_WORKSPACE;
   AttnParams p{};
@@ -230,9 +234,11 @@ int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, cons
   hipError_t e;
   if (pl.mfma) {
     e = pl.gqa ? launch_attn_gqa_mfma_bf16(p, stream) : launch_attn_mfma_bf16(p, stream);
-    if (e == hipSuccess && pl.n_split > 1) e = launch_attn_combine(p, s.dtype, stream);
+    if (deferred) *deferred = p;
+    if (e == hipSuccess && pl.n_split > 1 && !deferred) e = launch_attn_combine(p, s.dtype, stream);
   } else {
     e = launch_attn_simple(p, s.dtype, stream);
+    if (deferred) deferred->n_split = 1;
   }
   return e == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
 }
@@ -373,7 +379,26 @@ int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void*
 // Workspace of sdllm_block_step: [0, base) is shared by the attention partials and the scoring
 // buffers (used one after the other on the stream); the fused row statistics of the cache-update
 // step live behind it because they are written by the attention and read by the scoring.
-struct BlockStepWs { size_t base, stats_bytes; int stats_parts; bool fuse; };
+// Argument checks and launch parameters of the gather (k_total > 0).
+int32_t compact_params(const sdllm_shape_t& s, const void* k_full, const void* v_full, const int32_t* idx, void* k_cache,
+                       void* v_cache, CompactParams& p) {
+  if (!k_full || !v_full || !idx || !k_cache || !v_cache) return SDLLM_ERR_INVALID_ARG;
+  if (!aligned16(k_full) || !aligned16(v_full) || !aligned16(k_cache) || !aligned16(v_cache))
+    return SDLLM_ERR_INVALID_ARG;
+  if (!row_stride_ok(s.kv_stride, s.head_dim) || !row_stride_ok(s.cache_stride, s.head_dim))
+    return SDLLM_ERR_INVALID_ARG;
+  const int es = elem_size(s.dtype);
+  p.k = k_full; p.v = v_full; p.idx = idx; p.kc = k_cache; p.vc = v_cache;
+  p.s_sb = s.kv_stride[0] * es; p.s_sh = s.kv_stride[1] * es; p.s_sr = s.kv_stride[2] * es;
+  p.c_sb = s.cache_stride[0] * es; p.c_sh = s.cache_stride[1] * es; p.c_sr = s.cache_stride[2] * es;
+  p.batch = s.batch; p.hkv = s.n_kv_heads; p.k_total = counts_of(s).k_total; p.seq_len = s.seq_len;
+  p.row_bytes = s.head_dim * es;
+  return SDLLM_OK;
+}
+
+// With split keys at the cache-update step the merge of the splits runs in the compaction's launch, so
+// the attention partials stay alive through scoring and selection: those then work behind them (score_off).
+struct BlockStepWs { size_t base, stats_bytes, score_off; int stats_parts; bool fuse; };
 
 BlockStepWs plan_block_step(const sdllm_shape_t& s) {
   const Counts c = counts_of(s);
@@ -381,9 +406,10 @@ BlockStepWs plan_block_step(const sdllm_shape_t& s) {
   const AttnPlan sparse = plan_attn(s, c.k_total, s.cache_stride[2], s.block_len, s.blk_stride[2]);
   const ScorePlan sc = plan_score(s);
   BlockStepWs w{};
+  w.score_off = dense.mfma && dense.n_split > 1 && c.k_total > 0 ? align_up(dense.ws_bytes()) : 0;
   w.base = dense.ws_bytes();
   if (sparse.ws_bytes() > w.base) w.base = sparse.ws_bytes();
-  if (sc.ws_bytes() > w.base) w.base = sc.ws_bytes();
+  if (w.score_off + sc.ws_bytes() > w.base) w.base = w.score_off + sc.ws_bytes();
   w.base = align_up(w.base);
   w.fuse = dense.mfma && sc.mfma && s.score_mode == SDLLM_SOFTMAX_MEAN && c.n_cand > 0;
   w.stats_parts = dense.n_split;
@@ -498,21 +524,10 @@ int32_t sdllm_compact_kv(const sdllm_shape_t* shape, const void* k_full, const v
                          void* k_cache, void* v_cache, void* stream) {
   const int32_t st = check_shape(shape);
   if (st != SDLLM_OK) return st;
-  const sdllm_shape_t& s = *shape;
-  const Counts c = counts_of(s);
-  if (c.k_total == 0) return SDLLM_OK;
-  if (!k_full || !v_full || !idx || !k_cache || !v_cache) return SDLLM_ERR_INVALID_ARG;
-  if (!aligned16(k_full) || !aligned16(v_full) || !aligned16(k_cache) || !aligned16(v_cache))
-    return SDLLM_ERR_INVALID_ARG;
-  if (!row_stride_ok(s.kv_stride, s.head_dim) || !row_stride_ok(s.cache_stride, s.head_dim))
-    return SDLLM_ERR_INVALID_ARG;
-  const int es = elem_size(s.dtype);
+  if (counts_of(*shape).k_total == 0) return SDLLM_OK;
   CompactParams p{};
-  p.k = k_full; p.v = v_full; p.idx = idx; p.kc = k_cache; p.vc = v_cache;
-  p.s_sb = s.kv_stride[0] * es; p.s_sh = s.kv_stride[1] * es; p.s_sr = s.kv_stride[2] * es;
-  p.c_sb = s.cache_stride[0] * es; p.c_sh = s.cache_stride[1] * es; p.c_sr = s.cache_stride[2] * es;
-  p.batch = s.batch; p.hkv = s.n_kv_heads; p.k_total = c.k_total; p.seq_len = s.seq_len;
-  p.row_bytes = s.head_dim * es;
+  const int32_t sp = compact_params(*shape, k_full, v_full, idx, k_cache, v_cache, p);
+  if (sp != SDLLM_OK) return sp;
   return launch_compact(p, (hipStream_t)stream) == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
 }
 
@@ -576,19 +591,32 @@ int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int3
   KvSegment a{k_in, v_in, s.kv_stride[0], s.kv_stride[1], s.kv_stride[2], s.seq_len};
   KvSegment b{nullptr, nullptr, 0, 0, 0, 0};
   const BlockStepWs w = plan_block_step(s);
+  AttnParams pending{};           // split-KV merge still to run (cache-update step only)
+  pending.n_split = 1;
+  AttnParams* defer = state == SDLLM_STATE_UPDATE && w.score_off > 0 ? &pending : nullptr;
   if (state == SDLLM_STATE_FULL || !w.fuse)
-    st = run_attn(s, q_blk, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+    st = run_attn(s, q_blk, a, b, out, ws, ws_bytes, (hipStream_t)stream, nullptr, 0, 0, defer);
   else {
     // cache-update step: the dense attention also leaves the scoring softmax's row statistics
     const int cand1 = s.evict_scope == SDLLM_EVICT_PREFIX_ONLY ? s.seq_len : s.block_off + s.block_len;
-    st = run_attn(s, q_blk, a, b, out, ws, w.base, (hipStream_t)stream, (float*)((char*)ws + w.base), s.block_off, cand1);
+    st = run_attn(s, q_blk, a, b, out, ws, w.base, (hipStream_t)stream, (float*)((char*)ws + w.base), s.block_off, cand1,
+                  defer);
   }
   if (st != SDLLM_OK || state == SDLLM_STATE_FULL) return st;
-  if (!row_stride_ok(s.q_stride, s.head_dim)) return SDLLM_ERR_INVALID_ARG;
-  st = score_select_impl(s, q_blk, k_in, idx, nullptr, nullptr, ws, w.base, (hipStream_t)stream,
-                         w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts);
-  if (st != SDLLM_OK) return st;
-  return sdllm_compact_kv(shape, k_in, v_in, idx, k_cache, v_cache, stream);
+  // from here on a pending merge must run whatever else fails: `out` is not complete without it
+  auto finish_pending = [&](int32_t status) {
+    if (pending.n_split > 1 && launch_attn_combine(pending, s.dtype, (hipStream_t)stream) != hipSuccess && status == SDLLM_OK)
+      return (int32_t)SDLLM_ERR_HIP;
+    return status;
+  };
+  if (!row_stride_ok(s.q_stride, s.head_dim)) return finish_pending(SDLLM_ERR_INVALID_ARG);
+  st = score_select_impl(s, q_blk, k_in, idx, nullptr, nullptr, (char*)ws + w.score_off, w.base - w.score_off,
+                         (hipStream_t)stream, w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts);
+  if (st != SDLLM_OK) return finish_pending(st);
+  if (pending.n_split == 1) return sdllm_compact_kv(shape, k_in, v_in, idx, k_cache, v_cache, stream);
+  CompactParams cp{};
+  if ((st = compact_params(s, k_in, v_in, idx, k_cache, v_cache, cp)) != SDLLM_OK) return finish_pending(st);
+  return launch_compact_combine(cp, pending, (hipStream_t)stream) == hipSuccess ? SDLLM_OK : SDLLM_ERR_HIP;
 }
 
 int32_t sdllm_dense_attn(const sdllm_shape_t* shape, const void* q_full, const int64_t* q_full_stride,

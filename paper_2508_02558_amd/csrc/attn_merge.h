@@ -84,4 +84,50 @@ __device__ __forceinline__ void store_piece(const RowPiece& r, T* out) {
   }
 }
 
+// Merge the n_split partial (max, sum, numerator) triples of each query row: TPI threads per (row, four
+// output columns), 16-byte loads, eight splits' loads in flight per thread (the partials mostly sit in
+// L2 / MALL, so the merge is bound by dependent round trips).  TPI = 1 for a few splits; with 16 and more
+// (long rows on few KV heads: 64 splits at the batch-1 32k-prompt grouped-query shape) four adjacent lanes
+// take every fourth split each and merge their pieces with two shuffles, which cuts the dependent batches
+// of loads from eight to two.
+// One block of kCombineThreads threads = kCombineThreads / TPI items of the [B*Hq, nq] x (d/4) item list.
+constexpr int kCombineThreads = 256;
+
+__host__ __device__ inline int combine_tpi(int n_split) { return n_split >= 16 ? 4 : 1; }
+
+// blocks of kCombineThreads threads that cover every item
+inline int64_t combine_blocks(const AttnParams& p) {
+  const int64_t threads = (int64_t)p.batch * p.hq * p.nq * (p.d >> 2) * combine_tpi(p.n_split);
+  return (threads + kCombineThreads - 1) / kCombineThreads;
+}
+
+template <typename T, int TPI>
+__device__ __forceinline__ void combine_block(const AttnParams& p, int block_id) {
+  const int total_rows = p.batch * p.hq * p.nq;
+  const int per_row = p.d >> 2;                                   // items per row
+  const int tid = block_id * kCombineThreads + threadIdx.x;
+  const int item = tid / TPI, sub = tid - item * TPI;
+  const int grow = item / per_row;                                // index into the [B*Hq, nq] row list
+  const bool valid = grow < total_rows;                           // whole groups of TPI lanes are valid or not
+  const int growc = valid ? grow : total_rows - 1;
+  const int c4 = valid ? (item - grow * per_row) << 2 : 0;
+  const int head = growc / p.nq;
+  const int row = growc - head * p.nq;
+  const int b = head / p.hq;
+  const int h = head - b * p.hq;
+  const float* ml = p.part_ml + (size_t)head * p.n_split * 2 * p.nq + row;        // split stride 2*nq
+  const float* po = p.part_o + ((size_t)head * p.n_split * p.nq + row) * p.d + c4;   // split stride nq*d
+  RowPiece r = fold_splits(ml, 2 * p.nq, p.nq, po, (size_t)p.nq * p.d, p.n_split, sub, TPI);
+#pragma unroll
+  for (int o = 1; o < TPI; o <<= 1) {
+    RowPiece other;
+    other.m = __shfl_xor(r.m, o);
+    other.l = __shfl_xor(r.l, o);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) other.o[c] = __shfl_xor(r.o[c], o);
+    merge_pieces(r, other);
+  }
+  if (valid && sub == 0) store_piece<T>(r, (T*)p.out + b * p.o_sb + h * p.o_sh + row * p.o_sr + c4);
+}
+
 }  // namespace sdllm

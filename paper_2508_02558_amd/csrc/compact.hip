@@ -2,16 +2,24 @@
 // equation; Alg. 1 steps 12-14).  Pure byte movement: each thread copies one 16-byte chunk of two
 // consecutive cache rows of K and of V, so a wavefront reads and writes whole rows with 16-byte
 // non-temporal accesses and has 4 loads in flight per lane (more in flight measured slower).
+//
+// At the cache-update step of a shape whose dense attention was split over the keys, the merge of those
+// splits has nothing to do with the gather and is only needed once the step returns: one launch then
+// runs both (compact_combine_kernel: the first blocks merge, the rest copy), which saves a launch
+// boundary and hides the merge under the copy.
+#include "attn_merge.h"
 #include "sdllm_internal.h"
 
 namespace sdllm {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kRowsPerThread = 2;
+constexpr int kCompactThreads = 256;
+static_assert(kCompactThreads == kCombineThreads, "the fused launch runs both bodies with one block size");
 
-__global__ __launch_bounds__(256) void compact_kernel(const CompactParams p) {
+__device__ __forceinline__ void compact_block(const CompactParams& p, int64_t block_id) {
   const int chunks = p.row_bytes >> 4;
-  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t gid = block_id * kCompactThreads + threadIdx.x;
   const int64_t rgroup = gid / chunks;
   const int c16 = (int)(gid - rgroup * chunks) << 4;
   const int64_t total_rows = (int64_t)p.batch * p.hkv * p.k_total;
@@ -52,13 +60,37 @@ __global__ __launch_bounds__(256) void compact_kernel(const CompactParams p) {
   }
 }
 
-hipError_t launch_compact(const CompactParams& p, hipStream_t s) {
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactParams p) { compact_block(p, blockIdx.x); }
+
+// blocks [0, n_combine): split-KV merge of the attention described by `a` (bf16 output); the rest: the gather
+template <int TPI>
+__global__ __launch_bounds__(kCompactThreads) void compact_combine_kernel(const CompactParams p, const AttnParams a,
+                                                                          const int n_combine) {
+  if ((int)blockIdx.x < n_combine) combine_block<__bf16, TPI>(a, blockIdx.x);
+  else compact_block(p, (int64_t)blockIdx.x - n_combine);
+}
+
+static int64_t compact_blocks(const CompactParams& p) {
   const int64_t total_rows = (int64_t)p.batch * p.hkv * p.k_total;
-  if (total_rows == 0) return hipSuccess;
   const int chunks = p.row_bytes >> 4;
   const int64_t threads = ((total_rows + kRowsPerThread - 1) / kRowsPerThread) * chunks;
-  const int64_t blocks = (threads + 255) / 256;
-  hipLaunchKernelGGL(compact_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+  return (threads + kCompactThreads - 1) / kCompactThreads;
+}
+
+hipError_t launch_compact(const CompactParams& p, hipStream_t s) {
+  const int64_t blocks = compact_blocks(p);
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(compact_kernel, dim3((unsigned)blocks), dim3(kCompactThreads), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_combine(const CompactParams& p, const AttnParams& a, hipStream_t s) {
+  const int64_t n_combine = combine_blocks(a);
+  const int64_t blocks = n_combine + compact_blocks(p);
+  if (combine_tpi(a.n_split) == 4)
+    hipLaunchKernelGGL(compact_combine_kernel<4>, dim3((unsigned)blocks), dim3(kCompactThreads), 0, s, p, a, (int)n_combine);
+  else
+    hipLaunchKernelGGL(compact_combine_kernel<1>, dim3((unsigned)blocks), dim3(kCompactThreads), 0, s, p, a, (int)n_combine);
   return hipGetLastError();
 }
 

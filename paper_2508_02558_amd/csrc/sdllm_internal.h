@@ -164,6 +164,8 @@ hipError_t launch_select(const SelectParams& p, hipStream_t s);
 SelectWorkspace select_workspace(const SelectParams& p);
 int select_max_segment();
 hipError_t launch_compact(const CompactParams& p, hipStream_t s);
+// the gather plus the split-KV merge of a bf16 attention launch whose partials are still in the workspace
+hipError_t launch_compact_combine(const CompactParams& p, const AttnParams& a, hipStream_t s);
 hipError_t launch_dense_full_mfma_bf16(const DenseFullParams& p, hipStream_t s);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
 
