@@ -170,17 +170,11 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
     const int max_split = tiles / (heads <= 32 ? 7 : 11);
     if (n_split > max_split) n_split = max_split;
     if (n_split < 1) n_split = 1;
-#ifdef SDLLM_TUNING   // development builds only: launch-plan overrides from the environment
-    if (const char* e = getenv("SDLLM_T_NSPLIT")) { n_split = atoi(e); if (n_split > tiles) n_split = tiles; if (n_split < 1) n_split = 1; }
-#endif
     pl.tiles_per_split = (tiles + n_split - 1) / n_split;
     pl.waves = pl.tiles_per_split < kMaxWavesPerWg ? pl.tiles_per_split : kMaxWavesPerWg;
     // split workgroups: two tiles per wave when there are fewer than sixteen (28 heads x 69 tiles in 6
     // splits: 12.6 -> 12.35 us with six waves instead of eight; the in-workgroup merge is smaller)
     if (n_split > 1) { const int w2 = (pl.tiles_per_split + 1) / 2; pl.waves = w2 < kMaxWavesPerWg ? w2 : kMaxWavesPerWg; }
-#ifdef SDLLM_TUNING
-    if (const char* e = getenv("SDLLM_T_WAVES")) { pl.waves = atoi(e); if (pl.waves > pl.tiles_per_split) pl.waves = pl.tiles_per_split; }
-#endif
     // One workgroup per head: fewer, longer-running waves measured faster than eight (smaller merge at
     // the end, 40-48 KB instead of 64 KB of loads in flight per CU).  With more heads than CUs four
     // waves let two workgroups share a CU, so one streams while the other merges and writes, and no
