@@ -199,6 +199,12 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
   return pl;
 }
 
+// Whether the dense launch of a cache-update step can also leave the saliency scores: multi-head attention
+// (one query head per KV head) on the one-workgroup-per-head kernel, no key splits, at least two waves.
+bool fuses_columns(const AttnPlan& pl, const sdllm_shape_t& s) {
+  return pl.mfma && !pl.gqa && pl.n_split == 1 && pl.waves >= 2 && s.n_q_heads == s.n_kv_heads;
+}
+
 // cand_ml != null (dense MFMA launches only): also emit the scoring pass's row statistics over the
 // candidate keys, n_split partials per query row.
 // deferred != null: when the keys are split over workgroups, leave the merge of the splits to the caller
@@ -206,7 +212,7 @@ AttnPlan plan_attn(const sdllm_shape_t& s, int32_t n0, int64_t sr0, int32_t n1, 
 // the same stream before the partials' workspace is reused); deferred->n_split == 1 says nothing is left.
 int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, const KvSegment& b, void* out, void* ws,
                  size_t ws_bytes, hipStream_t stream, float* cand_ml = nullptr, int cand0_end = 0, int cand1_begin = 0,
-                 AttnParams* deferred = nullptr) {
+                 AttnParams* deferred = nullptr, float* score_out = nullptr, int score_stride = 0) {
   const AttnPlan pl = plan_attn(s, a.n, a.sr, b.n, b.sr);
   if (pl.ws_bytes() > 0 && (!ws || ws_bytes < pl.ws_bytes())) return SDLLM_ERR_WORKSPACE;
   AttnParams p{};
@@ -225,6 +231,10 @@ int32_t run_attn(const sdllm_shape_t& s, const void* q, const KvSegment& a, cons
   p.cand_ml = pl.mfma ? cand_ml : nullptr;
   p.cand0_end = cand0_end;
   p.cand1_begin = cand1_begin;
+  // the column sweep rides on the statistics launch of the one-workgroup-per-head kernel (fuses_columns below)
+  p.score_out = p.cand_ml ? score_out : nullptr;
+  p.score_stride = score_stride;
+  p.score_inv_count = 1.f / (float)(s.block_len * (s.n_q_heads / s.n_kv_heads));
   hipError_t e;
   if (pl.mfma) {
     e = pl.gqa ? launch_attn_gqa_mfma_bf16(p, stream) : launch_attn_mfma_bf16(p, stream);
@@ -317,9 +327,10 @@ int32_t check_q(const sdllm_shape_t& s, const void* q) {
 
 // Alg. 1 steps 2-10.  ext_ml != null: the softmax row statistics over the candidates were already
 // produced (ext_parts partials per row) and only the column reduction and the selection run.
+// scores_ready: the scores are in the workspace's score buffer already; only the selection runs.
 int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void* k_full, int32_t* idx_out,
                           float* pooled_out, float* score_out, void* ws, size_t ws_bytes, hipStream_t hs,
-                          float* ext_ml, int ext_parts) {
+                          float* ext_ml, int ext_parts, bool scores_ready = false) {
   const Counts c = counts_of(s);
   const ScorePlan pl = plan_score(s);
   if (!ws || ws_bytes < pl.ws_bytes() || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return SDLLM_ERR_WORKSPACE;
@@ -359,7 +370,8 @@ int32_t score_select_impl(const sdllm_shape_t& s, const void* q_blk, const void*
   sp.part_ml = ext_ml ? ext_ml : ml;
   sp.n_stat_part = ext_ml ? ext_parts : pl.n_part;
   sp.skip_stats = ext_ml != nullptr;
-  hipError_t e = pl.mfma ? launch_score_mfma_bf16(sp, hs) : launch_score_simple(sp, s.dtype, hs);
+  // scores_ready: the dense attention of this step already left the scores in the workspace's score buffer
+  hipError_t e = scores_ready ? hipSuccess : pl.mfma ? launch_score_mfma_bf16(sp, hs) : launch_score_simple(sp, s.dtype, hs);
   if (e != hipSuccess) return SDLLM_ERR_HIP;
 
   SelectParams q{};
@@ -392,7 +404,7 @@ int32_t compact_params(const sdllm_shape_t& s, const void* k_full, const void* v
 
 // With split keys at the cache-update step the merge of the splits runs in the compaction's launch, so
 // the attention partials stay alive through scoring and selection: those then work behind them (score_off).
-struct BlockStepWs { size_t base, stats_bytes, score_off; int stats_parts; bool fuse; };
+struct BlockStepWs { size_t base, stats_bytes, score_off; int stats_parts; bool fuse, fuse_cols; };
 
 BlockStepWs plan_block_step(const sdllm_shape_t& s) {
   const Counts c = counts_of(s);
@@ -407,6 +419,7 @@ BlockStepWs plan_block_step(const sdllm_shape_t& s) {
   w.base = align_up(w.base);
   w.fuse = dense.mfma && sc.mfma && s.score_mode == SDLLM_SOFTMAX_MEAN && c.n_cand > 0;
   w.stats_parts = dense.n_split;
+  w.fuse_cols = w.fuse && fuses_columns(dense, s);
   w.stats_bytes = w.fuse ? align_up((size_t)s.batch * s.n_q_heads * dense.n_split * 64 * sizeof(float)) : 0;
   return w;
 }
@@ -593,8 +606,9 @@ int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int3
   else {
     // cache-update step: the dense attention also leaves the scoring softmax's row statistics
     const int cand1 = s.evict_scope == SDLLM_EVICT_PREFIX_ONLY ? s.seq_len : s.block_off + s.block_len;
+    // ... and, where one workgroup owns a head, the saliency scores themselves (first buffer of the scoring workspace)
     st = run_attn(s, q_blk, a, b, out, ws, w.base, (hipStream_t)stream, (float*)((char*)ws + w.base), s.block_off, cand1,
-                  defer);
+                  defer, w.fuse_cols ? (float*)((char*)ws + w.score_off) : nullptr, c.n_cand);
   }
   if (st != SDLLM_OK || state == SDLLM_STATE_FULL) return st;
   // from here on a pending merge must run whatever else fails: `out` is not complete without it
@@ -605,7 +619,7 @@ int32_t sdllm_block_step(const sdllm_shape_t* shape, int32_t step_in_block, int3
   };
   if (!row_stride_ok(s.q_stride, s.head_dim)) return finish_pending(SDLLM_ERR_INVALID_ARG);
   st = score_select_impl(s, q_blk, k_in, idx, nullptr, nullptr, (char*)ws + w.score_off, w.base - w.score_off,
-                         (hipStream_t)stream, w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts);
+                         (hipStream_t)stream, w.fuse ? (float*)((char*)ws + w.base) : nullptr, w.stats_parts, w.fuse_cols);
   if (st != SDLLM_OK) return finish_pending(st);
   if (pending.n_split == 1) return sdllm_compact_kv(shape, k_in, v_in, idx, k_cache, v_cache, stream);
   CompactParams cp{};

@@ -38,7 +38,9 @@ constexpr int gqa_head_splits(int group) { return group >= 4 ? 2 : 1; }
 // gives the tile in memory) into registers, all threads together: piece c = tid + i*T of a tile is
 // 16-byte chunk c%16 of row c/16.  A tile never straddles the two key
 // segments, so its base is workgroup-uniform and K and V share offsets.
-template <int W, class TileMap>
+// KEEP_K: plain instead of non-temporal loads for K, because the scoring pass that follows a statistics
+// launch reads the same K rows again and finds them in L2 / the memory-side cache.
+template <int W, bool KEEP_K, class TileMap>
 __device__ __forceinline__ void gqa_load_stage(const SegPtrs& sp, int first_tile, int t_end, int tid, const TileMap& tile_of,
                                                u32x4 (&kreg)[gqa_stage_tiles(W) * gqa_chunks(W)],
                                                u32x4 (&vreg)[gqa_stage_tiles(W) * gqa_chunks(W)]) {
@@ -55,7 +57,8 @@ __device__ __forceinline__ void gqa_load_stage(const SegPtrs& sp, int first_tile
         int r = c >> 4;
         r = r < ts.rows ? r : ts.rows - 1;   // rows past the end re-read the last key; masked later
         const uint32_t off = (uint32_t)r * stride + ((c & 15) << 4);
-        kreg[j * CH + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.k + off));
+        const u32x4* kp = reinterpret_cast<const u32x4*>(ts.k + off);
+        kreg[j * CH + i] = KEEP_K ? *kp : __builtin_nontemporal_load(kp);
         vreg[j * CH + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ts.v + off));
       }
     }
@@ -177,9 +180,9 @@ void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
   auto tile_lds = [&](int j) { return smem + ((j / NT) & 1) * kStageBytes + (j % NT) * kKvTileBytes; };
 
   u32x4 kreg[NT * gqa_chunks(W)], vreg[NT * gqa_chunks(W)];
-  gqa_load_stage<W>(sp, t_begin, t_end, tid, tile_of, kreg, vreg);
+  gqa_load_stage<W, STATS>(sp, t_begin, t_end, tid, tile_of, kreg, vreg);
   gqa_store_stage<W>(smem, tid, kreg, vreg);
-  if (nstages > 1) gqa_load_stage<W>(sp, t_begin + NT, t_end, tid, tile_of, kreg, vreg);
+  if (nstages > 1) gqa_load_stage<W, STATS>(sp, t_begin + NT, t_end, tid, tile_of, kreg, vreg);
   __syncthreads();
 
   // Pipeline state between iterations: pb = softmax numerators of the current tile j (bf16), f = its V
@@ -198,7 +201,7 @@ void attn_gqa_mfma_bf16_kernel(const AttnParams p, const int head_splits) {
       const int s_new = (j + 2) / NT;
       gqa_store_stage<W>(smem + (s_new & 1) * kStageBytes, tid, kreg, vreg);
       __syncthreads();
-      if (s_new + 1 < nstages) gqa_load_stage<W>(sp, t_begin + (s_new + 1) * NT, t_end, tid, tile_of, kreg, vreg);
+      if (s_new + 1 < nstages) gqa_load_stage<W, STATS>(sp, t_begin + (s_new + 1) * NT, t_end, tid, tile_of, kreg, vreg);
     }
     if (!head_valid) return;
     if (j + 2 < nt) tile_k_load(tile_lds(j + 2), half, col, a);

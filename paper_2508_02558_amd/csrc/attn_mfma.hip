@@ -35,7 +35,10 @@ size_t attn_mfma_lds_bytes(int waves) { return (size_t)waves * kWaveLds; }
 // the bytes in flight).  Chosen for small grids, which are latency-bound; large grids saturate HBM and
 // run faster with the shallower alternating scheme.
 // SHARED_KV: the G query heads of a KV group run as separate workgroups (grouped-query attention on
-// a small grid); their K/V reads are then plain loads so that the siblings hit in L2.
+// a small grid); their K/V reads are then plain loads so that the siblings hit in L2.  K is also read
+// with plain loads by the statistics launches: the scoring that follows (the column sweep at the end of
+// this kernel, or the scoring kernel) reads the same rows again and finds part of them in L2 and the
+// memory-side cache (B=8 LLaDA shape, cache-update step: 234 -> 226 us).
 template <int NSEG, bool STATS, bool DEEP, bool SHARED_KV>
 __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
   TileSrc ts{};
   if (t < t_end) {
     ts = tile_src(sp, t, stride);
-    load_rows<!SHARED_KV>(ts.k, ts.rows, stride, lane, reg);
+    load_rows<!(SHARED_KV || STATS)>(ts.k, ts.rows, stride, lane, reg);
     if (DEEP) load_rows<!SHARED_KV>(ts.v, ts.rows, stride, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
   }
 
@@ -98,7 +101,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
       wave_lds_sync();
       if (tn < t_end) {                              // both tensors of tile t+1 fly during tile t
         ts = tile_src(sp, tn, stride);
-        load_rows<!SHARED_KV>(ts.k, ts.rows, stride, lane, reg);
+        load_rows<!(SHARED_KV || STATS)>(ts.k, ts.rows, stride, lane, reg);
         load_rows<!SHARED_KV>(ts.v, ts.rows, stride, lane, reinterpret_cast<u32x4(&)[8]>(reg2));
       }
     } else {
@@ -139,7 +142,7 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
       wave_lds_sync();
       if (tn < t_end) {                              // K(t+1) flies during the PV product
         ts = tile_src(sp, tn, stride);
-        load_rows<!SHARED_KV>(ts.k, ts.rows, stride, lane, reg);
+        load_rows<!(SHARED_KV || STATS)>(ts.k, ts.rows, stride, lane, reg);
       }
     }
 
@@ -194,6 +197,11 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     }
     p.cand_ml[slot * 64 + lane] = mc;
     p.cand_ml[slot * 64 + 32 + lane] = lc;
+    if (p.score_out) {   // merged statistics for the column sweep below, in wave 0's own slots
+      float* st = reinterpret_cast<float*>(smem + 64 * kRowBytes) + 64;
+      st[lane] = mc;
+      st[32 + lane] = 1.f / lc;
+    }
   }
   // With the wave count a compile-time constant every LDS read of the merge (the waves' (max, sum) and the
   // up to ceil(16 / NW) slots this wave reduces) is requested before the first is used: one LDS round trip
@@ -259,6 +267,56 @@ __global__ __launch_bounds__(512) void attn_mfma_bf16_kernel(const AttnParams p)
     case 6: merge(std::integral_constant<int, 6>{}); break;
     case 7: merge(std::integral_constant<int, 7>{}); break;
     default: merge(std::integral_constant<int, 8>{}); break;
+  }
+
+  // Column sweep (cache-update step, MHA, no key splits): with the row statistics of the scoring softmax
+  // final, the workgroup walks its head's keys once more, LAST TILE FIRST (the most recently read K rows
+  // are the ones the memory-side cache may still hold), and leaves each candidate key's softmax-mean
+  // saliency score (Alg. 1 steps 5-6).  Same fragments as the attention, operands swapped: Q rows as the A
+  // operand, so a lane holds ONE key (lane % 32) against 16 query rows (8*(i/4) + 4*half + i%4).
+  if (STATS && p.score_out) {
+    __syncthreads();   // statistics visible; every wave is done with the parked accumulators
+    const float* st = reinterpret_cast<const float*>(smem + 64 * kRowBytes) + 64;
+    float row_m[16], row_il[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int row = (i >> 2) * 8 + half * 4 + (i & 3);
+      row_m[i] = st[row];
+      row_il[i] = st[32 + row];
+    }
+    float* score_row = p.score_out + (size_t)(b * p.hkv + g) * p.score_stride;
+    const int gap = p.cand1_begin - p.cand0_end;
+    int tc = ntiles - 1 - wave;
+    if (tc >= 0) {
+      ts = tile_src(sp, tc, stride);
+      load_rows<true>(ts.k, ts.rows, stride, lane, reg);
+    }
+    for (; tc >= 0; tc -= nw) {
+      const int rows = ts.rows;
+      store_rows(lds_k, lane, reg);
+      wave_lds_sync();
+      if (tc - nw >= 0) {
+        ts = tile_src(sp, tc - nw, stride);
+        load_rows<true>(ts.k, ts.rows, stride, lane, reg);
+      }
+      bf16x8 a[8];
+      tile_k_load(lds_k, half, col, a);
+      __builtin_amdgcn_sched_barrier(0);
+      f32x16 sc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], a[kk], sc, 0, 0, 0);
+      float total = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) total += __builtin_amdgcn_exp2f(__builtin_fmaf(sc[i], p.scale_log2, -row_m[i])) * row_il[i];
+      total += __shfl_xor(total, 32);
+      const int pos = tc * kTileKeys + col;
+      const bool cand = pos < p.cand0_end || pos >= p.cand1_begin;
+      if (half == 0 && col < rows && cand) score_row[pos < p.cand0_end ? pos : pos - gap] = total * p.score_inv_count;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
   }
 }
 

@@ -76,6 +76,13 @@ struct AttnParams {
   // kernels read their partial statistics in.  Null: not produced.
   float* cand_ml;
   int32_t cand0_end, cand1_begin;
+  // Optional second by-product of such a launch (one workgroup per head, no key splits, MHA): the
+  // softmax-mean saliency score of every candidate key (Alg. 1 steps 5-6), [B*Hkv, score_stride] floats,
+  // written by a second sweep over K that each workgroup runs once its row statistics are final.
+  // Null: not produced.
+  float* score_out;
+  int32_t score_stride;
+  float score_inv_count;    // 1 / (block queries x query heads per KV head)
 };
 
 // Scoring of the candidates K_f = Concat[K_{:o}, K_{o+b:}] against the block's queries.
