@@ -105,6 +105,17 @@ def test_llada_layer_bf16_block():
     _run_block(wl.WORKLOADS["llada8b_layer"], n_steps=3)
 
 
+@pytest.mark.parametrize("modes", [dict(), dict(evict_scope=B.SDLLM_EVICT_PREFIX_ONLY), dict(pool_mode=B.SDLLM_AVG_POOL)])
+def test_many_heads_unsplit_update_step_off_grid(modes):
+    # 160 heads: one workgroup per head and no key splits, so the cache-update step's dense launch also
+    # sweeps K for the saliency scores; the block starts at an odd offset (tiles straddle the block on
+    # both sides), once in the middle of the generation and once at its end (no suffix)
+    w = wl.WORKLOADS["llada8b_layer"].scaled(batch=5, prompt=1013)
+    _run_block(w, layer=1, block_index=3, n_steps=3, **modes)
+    if not modes:
+        _run_block(w, layer=2, block_index=w.n_blocks - 1, n_steps=3)
+
+
 def test_llada_layer_last_block_has_no_suffix():
     w = wl.WORKLOADS["llada8b_layer"].scaled(n_q_heads=4, n_kv_heads=4)
     _run_block(w, block_index=w.n_blocks - 1, n_steps=3)
