@@ -105,6 +105,7 @@ struct ScoreParams {
   float* part_ml;       // [B*Hq, n_stat_part, 2, nq]
   int32_t n_stat_part;  // partial (max, sum) pairs per query row in part_ml
   int32_t skip_stats;   // 1: part_ml was already filled (by the dense attention of the same step)
+  int32_t cols_follow;  // set by the launcher: the statistics kernel runs the column pass itself (n_part == 1)
   int32_t waves;
 };
 
